@@ -1,0 +1,216 @@
+#!/usr/bin/env python3
+"""Benchmark of the MOM prefill hot path on one MI355X.
+
+One "step" is one pass of the whole mini-sequence MLP (every mini-sequence: gate/up GEMM with
+the SiLU*up epilogue, then the down GEMM) over one synthetic Llama-3-8B-shaped layer input
+(S=32768, H=4096, I=14336, mini_seq=4096, bf16) that is already resident in HBM.  Prints ONE
+JSON line: whole-job TFLOP/s (6*S*H*I flop per step), the roofline of the dominant kernel
+measured with HIP events on the launch stream, and the CPU oracle timed on a bounded row sample.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+BF16_MFMA_PEAK_TFLOPS = 2500.0      # MI355X dense bf16 matrix peak (published figure)
+HBM_PEAK_GBPS = 8000.0
+
+
+def parse():
+    p = argparse.ArgumentParser()
+    p.add_argument("--gpus", type=int, default=1)
+    p.add_argument("--steps", type=int, default=20)
+    p.add_argument("--warmup", type=int, default=3)
+    p.add_argument("--workload", default="llama3_8b_32k")
+    p.add_argument("--mini-seq", type=int, default=None, help="override the workload's mini_seq")
+    p.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample; 0 skips")
+    p.add_argument("--extras", action="store_true", help="also time the LM head, the KV offload overlap and a mini_seq sweep")
+    return p.parse_args()
+
+
+def time_mlp(binding, torch, tensors, C, out, ws, steps, warmup):
+    x, wg, wu, wd = tensors
+    st = torch.cuda.current_stream()
+    for _ in range(warmup):
+        binding.mom_mlp_prefill(x, wg, wu, wd, C, out, ws, stream=st)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        binding.mom_mlp_prefill(x, wg, wu, wd, C, out, ws, stream=st)
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps
+
+
+def kernel_times(binding, torch, tensors, C, out, ws, S, reps):
+    """Average duration (s) of the gate/up and the down kernel, from HIP events recorded on the
+    launch stream around every kernel of `reps` whole passes."""
+    x, wg, wu, wd = tensors
+    st = torch.cuda.current_stream()
+    n = -(-S // C)
+    gu, dn = [], []
+    for _ in range(reps):
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(1 + 2 * n)]
+        for e in evs:
+            e.record(st)
+        binding.mom_mlp_prefill_events(x, wg, wu, wd, C, out, ws, evs, stream=st)
+        torch.cuda.synchronize()
+        for c in range(n):
+            gu.append(evs[2 * c].elapsed_time(evs[2 * c + 1]) * 1e-3)
+            dn.append(evs[2 * c + 1].elapsed_time(evs[2 * c + 2]) * 1e-3)
+    return sum(gu) / len(gu), sum(dn) / len(dn)
+
+
+def cpu_baseline(wl, tensors, synth, target_s):
+    """The oracle as it stands, timed on the host cores over a bounded sample of rows."""
+    import numpy as np
+    import oracle
+    x, wg, wu, wd = tensors
+    threads = oracle.num_threads()
+    wgb, wub, wdb = synth.bits(wg), synth.bits(wu), synth.bits(wd)
+    flop_row = 6.0 * wl.H * wl.I
+    probe = threads
+    xb = synth.bits(x[:probe])
+    t0 = time.perf_counter()
+    oracle.mlp_rows(xb, wgb, wub, wdb)
+    t_probe = time.perf_counter() - t0
+    rows = int(max(threads, min(4096, (target_s / max(t_probe, 1e-3)) * probe)))
+    rows -= rows % threads
+    xb = synth.bits(x[:rows])
+    t0 = time.perf_counter()
+    oracle.mlp_rows(xb, wgb, wub, wdb)
+    dt = time.perf_counter() - t0
+    return {"value": rows * flop_row / dt / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+            "sample": f"first {rows} of {wl.S} rows of the same workload, all {wl.I} intermediate columns "
+                      f"(includes widening the three weight matrices once), {dt:.1f} s",
+            "extrapolated_full_job_s": wl.S * flop_row / (rows * flop_row / dt)}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (the path has no cross-GPU step); run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2504_12526_amd import binding, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    binding.lib()                      # fail loudly if the HIP library is missing
+    dev = torch.device("cuda:0")
+    wl = synth.WORKLOADS[args.workload]
+    C = wl.mini_seq if args.mini_seq is None else args.mini_seq
+    S, H, I = wl.S, wl.H, wl.I
+    tensors = synth.mlp_inputs(wl, device=dev)
+    out = torch.empty((S, H), dtype=torch.bfloat16, device=dev)
+    ws_bytes = binding.mom_mlp_workspace_bytes(S, H, I, C)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    torch.cuda.synchronize()
+
+    sec = time_mlp(binding, torch, tensors, C, out, ws, args.steps, args.warmup)
+    flop = 6.0 * S * H * I
+    tflops = flop / sec / 1e12
+
+    t_gu, t_dn = kernel_times(binding, torch, tensors, C, out, ws, S, reps=max(2, min(5, args.steps)))
+    n_full = S // C
+    rows_per_launch = C if n_full else S
+    gu_tflops = 4.0 * rows_per_launch * H * I / t_gu / 1e12
+    dn_tflops = 2.0 * rows_per_launch * H * I / t_dn / 1e12
+
+    result = {
+        "metric": "mini-seq MLP prefill TFLOP/s (% bf16 MFMA peak) + peak workspace bytes",
+        "value": round(tflops, 2), "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(sec * 1e3, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{wl.name}: Llama-3-8B-shaped SwiGLU MLP layer S={S} H={H} I={I} mini_seq={C} bf16, "
+                               f"unit-RMS rows, weights N(0,0.02), seed {wl.seed}"
+                   if wl.name == "llama3_8b_32k" else f"{wl.name}: S={S} H={H} I={I} mini_seq={C} bf16",
+                   "S": S, "H": H, "I": I, "mini_seq": C, "mini_sequences": -(-S // C)},
+        "pct_bf16_mfma_peak": round(100.0 * tflops / BF16_MFMA_PEAK_TFLOPS, 2),
+        "workspace_bytes": ws_bytes, "unchunked_workspace_bytes": S * I * 2,
+        "roofline": {"bound": "mfma", "kernel": "gemm_kernel<EPI_GATEUP> (gate/up GEMM + SiLU*up epilogue)",
+                     "achieved": round(gu_tflops, 2), "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(gu_tflops / BF16_MFMA_PEAK_TFLOPS, 4), "traffic": None,
+                     "avg_launch_ms": round(t_gu * 1e3, 4), "flop_per_launch": 4.0 * rows_per_launch * H * I,
+                     "down_kernel": {"achieved": round(dn_tflops, 2), "avg_launch_ms": round(t_dn * 1e3, 4),
+                                     "frac": round(dn_tflops / BF16_MFMA_PEAK_TFLOPS, 4)}},
+    }
+
+    if args.extras:
+        result["extras"] = extras(args, binding, synth, torch, wl, tensors, out, dev)
+
+    if args.cpu_seconds > 0:
+        result["cpu_baseline"] = cpu_baseline(wl, tensors, synth, args.cpu_seconds)
+        for k in ("value", "extrapolated_full_job_s"):
+            result["cpu_baseline"][k] = float(f"{result['cpu_baseline'][k]:.4g}")
+    print(json.dumps(result))
+
+
+def extras(args, binding, synth, torch, wl, tensors, out, dev):
+    """Side measurements (not the headline): mini_seq sweep, LM-head GEMV bandwidth, KV offload overlap."""
+    S, H, I = wl.S, wl.H, wl.I
+    ex = {"sweep": []}
+    for C in (1024, 2048, 4096, 8192, 0):
+        nb = binding.mom_mlp_workspace_bytes(S, H, I, C)
+        ws = torch.empty(nb, dtype=torch.uint8, device=dev)
+        sec = time_mlp(binding, torch, tensors, C, out, ws, max(3, args.steps // 2), 2)
+        ex["sweep"].append({"mini_seq": C or S, "workspace_bytes": nb, "ms": round(sec * 1e3, 3),
+                            "tflops": round(6.0 * S * H * I / sec / 1e12, 1)})
+        del ws
+    # LM head GEMV at the Llama-3 vocabulary
+    lm = synth.Workload("lm", S=1, H=H, I=I, mini_seq=0, V=128256)
+    xl, wlm = synth.lmhead_inputs(lm, device=dev)
+    logits = torch.empty((lm.V,), dtype=torch.float32, device=dev)
+    st = torch.cuda.current_stream()
+    for _ in range(3):
+        binding.mom_lmhead_last(xl, wlm, logits)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = 20
+    e0.record(st)
+    for _ in range(reps):
+        binding.mom_lmhead_last(xl, wlm, logits)
+    e1.record(st)
+    torch.cuda.synchronize()
+    t = e0.elapsed_time(e1) * 1e-3 / reps
+    nbytes = lm.V * H * 2 + H * 2 + lm.V * 4
+    ex["lmhead"] = {"V": lm.V, "H": H, "us": round(t * 1e6, 2), "GBps": round(nbytes / t / 1e9, 1),
+                    "frac_hbm_peak": round(nbytes / t / 1e9 / HBM_PEAK_GBPS, 4)}
+    del wlm
+    # KV offload [S,8,128] x2 under the MLP
+    kvw = synth.Workload("kv", S=S, H=H, I=I, mini_seq=wl.mini_seq, kv_heads=8)
+    k, v = synth.kv_inputs(kvw, device=dev)
+    host = torch.empty(2 * k.numel(), dtype=torch.bfloat16).pin_memory()
+    side = torch.cuda.Stream()
+    order, done = torch.cuda.Event(), torch.cuda.Event()
+    order.record(st); done.record(st)
+    ws = torch.empty(binding.mom_mlp_workspace_bytes(S, H, I, wl.mini_seq), dtype=torch.uint8, device=dev)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    binding.mom_kv_offload(k, v, host, side, producer_stream=st, order_event=order, done_event=done)
+    done.synchronize()
+    t_copy = time.perf_counter() - t0
+    t_mlp = time_mlp(binding, torch, tensors, wl.mini_seq, out, ws, 5, 1)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    binding.mom_kv_offload(k, v, host, side, producer_stream=st, order_event=order, done_event=done)
+    for _ in range(5):
+        binding.mom_mlp_prefill(*tensors, wl.mini_seq, out, ws, stream=st)
+    torch.cuda.synchronize(); done.synchronize()
+    t_both = time.perf_counter() - t0
+    kvb = 2 * k.numel() * 2
+    ex["kv_offload"] = {"bytes": kvb, "copy_alone_ms": round(t_copy * 1e3, 3),
+                        "d2h_GBps": round(kvb / t_copy / 1e9, 1), "mlp_x5_alone_ms": round(5 * t_mlp * 1e3, 3),
+                        "mlp_x5_with_copy_ms": round(t_both * 1e3, 3)}
+    return ex
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,132 @@
+/*
+ * libmom — C ABI of the MI355X (gfx950) prefill hot path of MOM
+ * ("Memory-efficient Offloaded Mini-sequence Inference", arXiv 2504.12526).
+ *
+ * Conventions for every call
+ *   - bf16 tensors are arrays of 16-bit patterns (upper half of IEEE binary32),
+ *     row-major, densely packed.
+ *   - Unless a parameter says "host", pointers are DEVICE pointers on the
+ *     current HIP device.  The caller owns every buffer, stream and event.
+ *   - `stream` parameters are `hipStream_t` passed as `void*` (NULL = the
+ *     default stream).  Calls only ENQUEUE work; they never synchronise.
+ *     Results are valid once the caller has synchronised the stream (or the
+ *     event the call records).
+ *   - The library allocates nothing and keeps no state between calls.
+ *   - Return value: a `mom_status`; 0 is success.  Arguments are validated
+ *     before anything is enqueued, so a non-zero status other than
+ *     MOM_ERR_HIP means nothing was launched.
+ *
+ * Weight layout (the paper states only the mathematical shapes d->I, I->d):
+ * every weight is stored "output features x input features", so each
+ * contraction runs over the contiguous axis of both operands:
+ *   W_gate [I,H]   W_up [I,H]   W_down [H,I]   W_lm [V,H]
+ */
+#ifndef MOM_H
+#define MOM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    MOM_OK = 0,
+    MOM_ERR_NULL = 1,      /* a required pointer is NULL */
+    MOM_ERR_SHAPE = 2,     /* negative / zero / unsupported extent (H, I must be multiples of 32) */
+    MOM_ERR_ALIGN = 3,     /* a pointer is not 16-byte aligned */
+    MOM_ERR_ALIAS = 4,     /* an output or the workspace overlaps an input */
+    MOM_ERR_WORKSPACE = 5, /* workspace_bytes is smaller than mom_mlp_workspace_bytes() */
+    MOM_ERR_HIP = 6        /* the HIP runtime reported an error while enqueueing */
+} mom_status;
+
+/* Human-readable, static string for a status value. */
+const char *mom_status_string(int status);
+
+/*
+ * Bytes of workspace mom_mlp_prefill needs: C*I*2 with C = mini_seq if
+ * 0 < mini_seq < S, else S.  This is the mini-sequence intermediate of the
+ * paper's Eq. 3 (one C x I bf16 tensor), against S*I*2 for the full-sequence
+ * evaluation of Eq. 1.  Returns 0 for S <= 0 or invalid H / I / mini_seq.
+ */
+size_t mom_mlp_workspace_bytes(int64_t S, int64_t H, int64_t I, int64_t mini_seq);
+
+/*
+ * Mini-sequence SwiGLU MLP (Algorithm 1, else-branch; Section 3.3 "Llama MLP
+ * Layer"):
+ *     out = ( silu(x W_gate^T) .* (x W_up^T) ) W_down^T
+ * evaluated over ceil(S/C) mini-sequences of C = mini_seq rows (the last one
+ * shorter when C does not divide S); each mini-sequence's C x I intermediate is
+ * written to `workspace` and consumed before the next one overwrites it, and its
+ * output rows land directly at their place in `out` (the concat).
+ *
+ *   x        [S,H] bf16      in
+ *   W_gate   [I,H] bf16      in
+ *   W_up     [I,H] bf16      in
+ *   W_down   [H,I] bf16      in
+ *   out      [S,H] bf16      out
+ *   workspace  at least mom_mlp_workspace_bytes(S,H,I,mini_seq) bytes, scratch
+ *   mini_seq   rows per mini-sequence; 0 or >= S evaluates the whole sequence
+ *              at once through the same kernels (workspace S*I*2 bytes)
+ *
+ * Arithmetic: bf16 operands, fp32 accumulation on the matrix cores, SiLU and
+ * the gate*up product in fp32, one round-to-nearest-even to bf16 into the
+ * workspace, fp32 accumulation of the down projection, one rounding to bf16.
+ * Every output row is computed by an instruction sequence that does not depend
+ * on mini_seq or on the row's position, so any two values of mini_seq give
+ * bit-identical `out`.
+ *
+ * S = 0 is a no-op returning MOM_OK.  H and I must be positive multiples of 32.
+ * All work is enqueued on `stream` in order (2 kernels per mini-sequence).
+ */
+int mom_mlp_prefill(const void *x, const void *W_gate, const void *W_up, const void *W_down,
+                    int64_t S, int64_t H, int64_t I, int64_t mini_seq,
+                    void *out, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * The same computation with a HIP event recorded on `stream` before the first
+ * kernel and after every kernel: events[0], then for mini-sequence c the event
+ * events[1+2c] after its gate/up kernel and events[2+2c] after its down kernel.
+ * `events` is a host array of n_events `hipEvent_t` created by the caller;
+ * n_events must be at least 1 + 2*ceil(S/C).  For per-kernel timing only.
+ */
+int mom_mlp_prefill_events(const void *x, const void *W_gate, const void *W_up, const void *W_down,
+                           int64_t S, int64_t H, int64_t I, int64_t mini_seq,
+                           void *out, void *workspace, size_t workspace_bytes, void *stream,
+                           void **events, int64_t n_events);
+
+/*
+ * Last-token LM head (Algorithm 1, if-branch; Section 3.3: one projected token
+ * needs V outputs, not S*V):
+ *     logits[v] = sum_k x_last[k] * W_lm[v,k]
+ *   x_last [H] bf16 in,  W_lm [V,H] bf16 in,  logits [V] fp32 out.
+ * fp32 accumulation, fp32 result (no rounding before an argmax / softmax).
+ * H must be a positive multiple of 32 and at most 16384; V = 0 is a no-op.
+ */
+int mom_lmhead_last(const void *x_last, const void *W_lm, int64_t V, float *logits,
+                    int64_t H, void *stream);
+
+/*
+ * KV-cache offload of one layer (Algorithm 1 "offload"; Section 3.2): byte-exact
+ * asynchronous copy of k then v (bytes_each bytes each, device) to
+ * `pinned_host` (host, page-locked, at least 2*bytes_each bytes; k at offset 0,
+ * v at offset bytes_each) on `stream`, meant to be a side stream so the copy
+ * runs under the MLP kernels.
+ *   producer_stream  if not NULL, an event is recorded there first and `stream`
+ *                    waits for it, so the copy starts after the work that
+ *                    produced k and v (requires `order_event`)
+ *   order_event      hipEvent_t used for that ordering; may be NULL only when
+ *                    producer_stream is NULL
+ *   done_event       if not NULL, recorded on `stream` after both copies; the
+ *                    device k/v may be reused once it has completed
+ * bytes_each = 0 is a no-op (events are still recorded).
+ */
+int mom_kv_offload(const void *k, const void *v, void *pinned_host, void *stream,
+                   size_t bytes_each, void *producer_stream, void *order_event,
+                   void *done_event);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOM_H */

@@ -1,0 +1,172 @@
+// libmom: C ABI over the gfx950 kernels of the MOM prefill hot path (see include/mom.h).
+//
+// Host side: argument validation, the mini-sequence driver (Algorithm 1, else-branch), the
+// last-token LM head launch and the KV offload copies.  Nothing here allocates or synchronises.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "mom.h"
+#include "mom_gemm.hip.inc"
+#include "mom_gemv.hip.inc"
+
+namespace {
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+inline bool overlaps(const void* a, size_t na, const void* b, size_t nb) {
+    if (na == 0 || nb == 0) return false;
+    uintptr_t a0 = reinterpret_cast<uintptr_t>(a), b0 = reinterpret_cast<uintptr_t>(b);
+    return a0 < b0 + nb && b0 < a0 + na;
+}
+
+inline int64_t effective_chunk(int64_t S, int64_t mini_seq) {
+    return (mini_seq <= 0 || mini_seq > S) ? S : mini_seq;
+}
+
+int validate_mlp(const void* x, const void* wg, const void* wu, const void* wd, int64_t S, int64_t H,
+                 int64_t I, int64_t mini_seq, const void* out, const void* ws, size_t ws_bytes) {
+    if (S < 0 || H <= 0 || I <= 0 || mini_seq < 0) return MOM_ERR_SHAPE;
+    if ((H % 32) != 0 || (I % 32) != 0) return MOM_ERR_SHAPE;
+    if (S > (int64_t)0x7fffff00 || H > (1 << 20) || I > (1 << 20)) return MOM_ERR_SHAPE;
+    if (S == 0) return MOM_OK;
+    if (!x || !wg || !wu || !wd || !out || !ws) return MOM_ERR_NULL;
+    if (!aligned16(x) || !aligned16(wg) || !aligned16(wu) || !aligned16(wd) || !aligned16(out) ||
+        !aligned16(ws))
+        return MOM_ERR_ALIGN;
+    const size_t need = mom_mlp_workspace_bytes(S, H, I, mini_seq);
+    if (ws_bytes < need) return MOM_ERR_WORKSPACE;
+    const size_t xb = (size_t)S * H * 2, wb = (size_t)H * I * 2;
+    const void* ins[4] = {x, wg, wu, wd};
+    const size_t inb[4] = {xb, wb, wb, wb};
+    for (int i = 0; i < 4; ++i)
+        if (overlaps(out, xb, ins[i], inb[i]) || overlaps(ws, need, ins[i], inb[i])) return MOM_ERR_ALIAS;
+    if (overlaps(out, xb, ws, need)) return MOM_ERR_ALIAS;
+    return MOM_OK;
+}
+
+template <int EPI>
+hipError_t launch_gemm(const unsigned short* X, const unsigned short* W0, const unsigned short* W1,
+                       unsigned short* O, int M, int N, int K, hipStream_t st) {
+    momk::GemmArgs a;
+    a.X = X; a.W0 = W0; a.W1 = W1; a.O = O;
+    a.M = M; a.N = N; a.K = K;
+    const int tile_n = (EPI == momk::EPI_GATEUP) ? momk::kBW / 2 : momk::kBW;
+    a.tiles_m = (M + momk::kBM - 1) / momk::kBM;
+    a.tiles_n = (N + tile_n - 1) / tile_n;
+    a.group_m = 4;
+    const int64_t tiles = (int64_t)a.tiles_m * a.tiles_n;
+    a.tiles_per_xcd = (int)((tiles + 7) / 8);
+    dim3 grid((unsigned)(a.tiles_per_xcd * 8)), block(momk::kThreads);
+    hipLaunchKernelGGL(momk::gemm_kernel<EPI>, grid, block, 0, st, a);
+    return hipGetLastError();
+}
+
+int mlp_driver(const void* x, const void* wg, const void* wu, const void* wd, int64_t S, int64_t H,
+               int64_t I, int64_t mini_seq, void* out, void* ws, size_t ws_bytes, void* stream,
+               void** events, int64_t n_events) {
+    int rc = validate_mlp(x, wg, wu, wd, S, H, I, mini_seq, out, ws, ws_bytes);
+    if (rc != MOM_OK || S == 0) return rc;
+    const int64_t C = effective_chunk(S, mini_seq);
+    const int64_t n = (S + C - 1) / C;
+    if (events && n_events < 1 + 2 * n) return MOM_ERR_SHAPE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const unsigned short* xs = static_cast<const unsigned short*>(x);
+    unsigned short* os = static_cast<unsigned short*>(out);
+    unsigned short* w = static_cast<unsigned short*>(ws);
+    if (events && hipEventRecord(static_cast<hipEvent_t>(events[0]), st) != hipSuccess) return MOM_ERR_HIP;
+    // Algorithm 1, else-branch: O_i = MLP(A_i) for each mini-sequence, O_i written at its rows of O.
+    for (int64_t c = 0; c < n; ++c) {
+        const int64_t r0 = c * C;
+        const int rows = (int)((r0 + C <= S) ? C : (S - r0));
+        if (launch_gemm<momk::EPI_GATEUP>(xs + r0 * H, static_cast<const unsigned short*>(wg),
+                                          static_cast<const unsigned short*>(wu), w, rows, (int)I, (int)H,
+                                          st) != hipSuccess)
+            return MOM_ERR_HIP;
+        if (events && hipEventRecord(static_cast<hipEvent_t>(events[1 + 2 * c]), st) != hipSuccess)
+            return MOM_ERR_HIP;
+        if (launch_gemm<momk::EPI_DOWN>(w, static_cast<const unsigned short*>(wd), nullptr, os + r0 * H, rows,
+                                        (int)H, (int)I, st) != hipSuccess)
+            return MOM_ERR_HIP;
+        if (events && hipEventRecord(static_cast<hipEvent_t>(events[2 + 2 * c]), st) != hipSuccess)
+            return MOM_ERR_HIP;
+    }
+    return MOM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* mom_status_string(int status) {
+    switch (status) {
+        case MOM_OK: return "ok";
+        case MOM_ERR_NULL: return "null pointer";
+        case MOM_ERR_SHAPE: return "bad shape (H and I must be positive multiples of 32)";
+        case MOM_ERR_ALIGN: return "pointer not 16-byte aligned";
+        case MOM_ERR_ALIAS: return "output or workspace overlaps an input";
+        case MOM_ERR_WORKSPACE: return "workspace too small";
+        case MOM_ERR_HIP: return "HIP runtime error";
+        default: return "unknown status";
+    }
+}
+
+size_t mom_mlp_workspace_bytes(int64_t S, int64_t H, int64_t I, int64_t mini_seq) {
+    if (S <= 0 || H <= 0 || I <= 0 || mini_seq < 0) return 0;
+    return (size_t)effective_chunk(S, mini_seq) * (size_t)I * 2;
+}
+
+int mom_mlp_prefill(const void* x, const void* W_gate, const void* W_up, const void* W_down, int64_t S,
+                    int64_t H, int64_t I, int64_t mini_seq, void* out, void* workspace,
+                    size_t workspace_bytes, void* stream) {
+    return mlp_driver(x, W_gate, W_up, W_down, S, H, I, mini_seq, out, workspace, workspace_bytes, stream,
+                      nullptr, 0);
+}
+
+int mom_mlp_prefill_events(const void* x, const void* W_gate, const void* W_up, const void* W_down,
+                           int64_t S, int64_t H, int64_t I, int64_t mini_seq, void* out, void* workspace,
+                           size_t workspace_bytes, void* stream, void** events, int64_t n_events) {
+    if (!events) return MOM_ERR_NULL;
+    return mlp_driver(x, W_gate, W_up, W_down, S, H, I, mini_seq, out, workspace, workspace_bytes, stream,
+                      events, n_events);
+}
+
+int mom_lmhead_last(const void* x_last, const void* W_lm, int64_t V, float* logits, int64_t H, void* stream) {
+    if (V < 0 || H <= 0 || (H % 32) != 0 || H > momk::kGemvMaxH || V > (int64_t)0x7fffff00) return MOM_ERR_SHAPE;
+    if (V == 0) return MOM_OK;
+    if (!x_last || !W_lm || !logits) return MOM_ERR_NULL;
+    if (!aligned16(x_last) || !aligned16(W_lm) || !aligned16(logits)) return MOM_ERR_ALIGN;
+    if (overlaps(logits, (size_t)V * 4, x_last, (size_t)H * 2) ||
+        overlaps(logits, (size_t)V * 4, W_lm, (size_t)V * H * 2))
+        return MOM_ERR_ALIAS;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int rows_per_block = momk::kGemvWaves * momk::kGemvRowsPerWave;
+    int64_t blocks = (V + rows_per_block - 1) / rows_per_block;
+    const int64_t max_blocks = 256 * 8;          // a few resident workgroups per CU; each loops over rows
+    if (blocks > max_blocks) blocks = max_blocks;
+    hipLaunchKernelGGL(momk::lmhead_gemv_kernel, dim3((unsigned)blocks), dim3(momk::kGemvWaves * 64), 0, st,
+                       static_cast<const unsigned short*>(x_last), static_cast<const unsigned short*>(W_lm),
+                       logits, (int)V, (int)H);
+    return hipGetLastError() == hipSuccess ? MOM_OK : MOM_ERR_HIP;
+}
+
+int mom_kv_offload(const void* k, const void* v, void* pinned_host, void* stream, size_t bytes_each,
+                   void* producer_stream, void* order_event, void* done_event) {
+    if (bytes_each != 0 && (!k || !v || !pinned_host)) return MOM_ERR_NULL;
+    if (producer_stream && !order_event) return MOM_ERR_NULL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (producer_stream) {
+        hipEvent_t ev = static_cast<hipEvent_t>(order_event);
+        if (hipEventRecord(ev, static_cast<hipStream_t>(producer_stream)) != hipSuccess) return MOM_ERR_HIP;
+        if (hipStreamWaitEvent(st, ev, 0) != hipSuccess) return MOM_ERR_HIP;
+    }
+    if (bytes_each != 0) {
+        unsigned char* dst = static_cast<unsigned char*>(pinned_host);
+        if (hipMemcpyAsync(dst, k, bytes_each, hipMemcpyDeviceToHost, st) != hipSuccess) return MOM_ERR_HIP;
+        if (hipMemcpyAsync(dst + bytes_each, v, bytes_each, hipMemcpyDeviceToHost, st) != hipSuccess)
+            return MOM_ERR_HIP;
+    }
+    if (done_event && hipEventRecord(static_cast<hipEvent_t>(done_event), st) != hipSuccess) return MOM_ERR_HIP;
+    return MOM_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,319 @@
+"""GPU parity tests: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs, plus the properties the paper claims (mini-sequence == full-sequence output)."""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2504_12526_amd import binding, synth
+
+pytestmark = pytest.mark.gpu
+
+REL_TOL = 2e-2      # stated bar: max relative error 2e-2 for bf16 in/out with fp32 accumulation
+
+
+def _dev():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    return torch.device("cuda:0")
+
+
+def _f32(bits_or_tensor):
+    if isinstance(bits_or_tensor, torch.Tensor):
+        return bits_or_tensor.to(torch.float32).cpu().numpy()
+    return synth.bits_to_f64(bits_or_tensor).astype(np.float32)
+
+
+def assert_close_to_oracle(got, ref, what=""):
+    """got: float32 array of the GPU's bf16/fp32 values; ref: oracle float32.
+    Normwise: max|g-r| <= 2e-2 * max|r|.  Element-wise: |g-r| <= 2e-2*|r| + 2e-2*rms(r)
+    (plain element-wise relative error is ill-posed where r ~ 0)."""
+    got = np.asarray(got, dtype=np.float64); ref = np.asarray(ref, dtype=np.float64)
+    assert got.shape == ref.shape, what
+    assert np.all(np.isfinite(got)), what
+    if ref.size == 0:
+        return
+    err = np.abs(got - ref)
+    scale = np.abs(ref).max()
+    rms = np.sqrt(np.mean(ref * ref))
+    assert err.max() <= REL_TOL * scale, f"{what}: normwise {err.max() / scale:.3e}"
+    bad = err > REL_TOL * np.abs(ref) + REL_TOL * rms
+    assert not bad.any(), f"{what}: {bad.sum()} elements outside tolerance, worst {err.max():.3e}"
+
+
+def run_mlp(x, wg, wu, wd, mini_seq, stream=None):
+    S, H = x.shape
+    I = wg.shape[0]
+    out = torch.empty((S, H), dtype=torch.bfloat16, device=x.device)
+    nbytes = binding.mom_mlp_workspace_bytes(S, H, I, mini_seq)
+    ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=x.device)
+    binding.mom_mlp_prefill(x, wg, wu, wd, mini_seq, out, ws, stream=stream)
+    torch.cuda.synchronize()
+    return out, nbytes
+
+
+def bits_equal(a, b):
+    return torch.equal(a.view(torch.int16), b.view(torch.int16))
+
+
+# ------------------------------------------------------------------ small shapes, full compare
+
+def test_tiny_workload_matches_oracle_and_unchunked():
+    dev = _dev()
+    wl = synth.WORKLOADS["tiny"]
+    x, wg, wu, wd = synth.mlp_inputs(wl)                      # CPU-generated, seed 0
+    ref = oracle.mlp_rows(*(synth.bits(t) for t in (x, wg, wu, wd)))
+    xd, wgd, wud, wdd = (t.to(dev) for t in (x, wg, wu, wd))
+    out, nbytes = run_mlp(xd, wgd, wud, wdd, wl.mini_seq)
+    assert nbytes == wl.mini_seq * wl.I * 2
+    assert_close_to_oracle(_f32(out), ref, "tiny mini-seq")
+    full, nfull = run_mlp(xd, wgd, wud, wdd, 0)
+    assert nfull == wl.S * wl.I * 2
+    assert bits_equal(out, full)
+
+
+@pytest.mark.parametrize("S,H,I", [(300, 96, 160), (257, 256, 288), (1, 64, 32), (513, 32, 1056), (40, 544, 96)])
+def test_ragged_shapes_match_oracle(S, H, I):
+    dev = _dev()
+    wl = synth.Workload("ragged", S=S, H=H, I=I, mini_seq=0, seed=S + H + I, w_std=0.05)
+    x, wg, wu, wd = synth.mlp_inputs(wl)
+    ref = oracle.mlp_rows(*(synth.bits(t) for t in (x, wg, wu, wd)))
+    xd, wgd, wud, wdd = (t.to(dev) for t in (x, wg, wu, wd))
+    full, _ = run_mlp(xd, wgd, wud, wdd, 0)
+    assert_close_to_oracle(_f32(full), ref, f"S={S} H={H} I={I}")
+    for C in (1, 7, 100, 256, S, S + 3):
+        if C == 1 and S > 64:
+            continue
+        out, nbytes = run_mlp(xd, wgd, wud, wdd, C)
+        assert nbytes == min(C, S) * I * 2
+        assert bits_equal(out, full), f"C={C}"
+
+
+def test_row_permutation_and_independence_on_gpu():
+    dev = _dev()
+    wl = synth.Workload("perm", S=700, H=128, I=384, mini_seq=0, seed=11, w_std=0.05)
+    x, wg, wu, wd = (t.to(dev) for t in synth.mlp_inputs(wl))
+    base, _ = run_mlp(x, wg, wu, wd, 200)
+    g = torch.Generator().manual_seed(3)
+    perm = torch.randperm(wl.S, generator=g).to(dev)
+    outp, _ = run_mlp(x[perm].contiguous(), wg, wu, wd, 333)
+    assert bits_equal(outp, base[perm].contiguous())
+    x2 = x.clone(); x2[123] = x[5]
+    out2, _ = run_mlp(x2, wg, wu, wd, 64)
+    diff = (out2.view(torch.int16) != base.view(torch.int16)).any(dim=1)
+    assert diff.sum().item() == 1 and bool(diff[123])
+    assert bits_equal(out2[123:124].contiguous(), base[5:6].contiguous())
+
+
+def test_zero_inputs_and_scaling_on_gpu():
+    dev = _dev()
+    wl = synth.Workload("zeros", S=130, H=64, I=96, mini_seq=0, seed=5, w_std=0.1)
+    x, wg, wu, wd = (t.to(dev) for t in synth.mlp_inputs(wl))
+    base, _ = run_mlp(x, wg, wu, wd, 50)
+    z, _ = run_mlp(x, wg, torch.zeros_like(wu), wd, 50)
+    assert torch.count_nonzero(z.to(torch.float32)).item() == 0
+    z, _ = run_mlp(torch.zeros_like(x), wg, wu, wd, 50)
+    assert torch.count_nonzero(z.to(torch.float32)).item() == 0
+    d2, _ = run_mlp(x, wg, wu, (wd.to(torch.float32) * 2).to(torch.bfloat16), 50)
+    assert bits_equal(d2, (base.to(torch.float32) * 2).to(torch.bfloat16))
+
+
+def test_silu_extremes_give_no_nan():
+    dev = _dev()
+    S, H, I = 64, 32, 32
+    x = torch.zeros((S, H), dtype=torch.bfloat16); x[:, 0] = 1.0
+    wg = torch.zeros((I, H), dtype=torch.bfloat16)
+    wg[:, 0] = torch.linspace(-3e4, 3e4, I).to(torch.bfloat16)           # gate pre-activations up to +-3e4
+    wu = torch.zeros((I, H), dtype=torch.bfloat16); wu[:, 0] = 1.0
+    wd = torch.eye(H, I, dtype=torch.bfloat16)
+    ref = oracle.mlp_rows(*(synth.bits(t) for t in (x, wg, wu, wd)))
+    out, _ = run_mlp(x.to(dev), wg.to(dev), wu.to(dev), wd.to(dev), 16)
+    assert_close_to_oracle(_f32(out), ref, "silu extremes")
+
+
+def test_empty_and_error_paths_on_gpu():
+    dev = _dev()
+    wl = synth.Workload("e", S=8, H=32, I=32, mini_seq=0)
+    x, wg, wu, wd = (t.to(dev) for t in synth.mlp_inputs(wl))
+    out = torch.empty_like(x)
+    ws = torch.empty(8 * 32 * 2, dtype=torch.uint8, device=dev)
+    assert binding.mom_mlp_prefill(x[:0], wg, wu, wd, 4, out[:0], ws) == binding.MOM_OK
+    small = torch.empty(16, dtype=torch.uint8, device=dev)
+    assert binding.mom_mlp_prefill(x, wg, wu, wd, 4, out, small, check=False) == binding.MOM_ERR_WORKSPACE
+    assert binding.mom_mlp_prefill(x, wg, wu, wd, 4, x, ws, check=False) == binding.MOM_ERR_ALIAS
+    torch.cuda.synchronize()
+
+
+def test_library_allocates_nothing():
+    dev = _dev()
+    wl = synth.Workload("mem", S=2048, H=256, I=1024, mini_seq=512, seed=2)
+    x, wg, wu, wd = (t.to(dev) for t in synth.mlp_inputs(wl))
+    out = torch.empty_like(x)
+    ws = torch.empty(binding.mom_mlp_workspace_bytes(wl.S, wl.H, wl.I, wl.mini_seq), dtype=torch.uint8, device=dev)
+    binding.mom_mlp_prefill(x, wg, wu, wd, wl.mini_seq, out, ws)
+    torch.cuda.synchronize()
+    free0, _ = torch.cuda.mem_get_info()
+    peak0 = torch.cuda.max_memory_allocated()
+    for _ in range(3):
+        binding.mom_mlp_prefill(x, wg, wu, wd, wl.mini_seq, out, ws)
+    torch.cuda.synchronize()
+    free1, _ = torch.cuda.mem_get_info()
+    assert free1 == free0 and torch.cuda.max_memory_allocated() == peak0
+
+
+# ------------------------------------------------------------------ LM head and last-token branch
+
+@pytest.mark.parametrize("V,H", [(4096, 256), (1001, 4096), (3, 32), (16, 3584), (5000, 416)])
+def test_lmhead_matches_oracle(V, H):
+    dev = _dev()
+    wl = synth.Workload("lm", S=1, H=H, I=32, mini_seq=0, V=V, seed=V % 97)
+    xl, w = synth.lmhead_inputs(wl)
+    ref = oracle.lmhead(synth.bits(xl), synth.bits(w))
+    logits = torch.full((V,), float("nan"), dtype=torch.float32, device=dev)
+    binding.mom_lmhead_last(xl.to(dev), w.to(dev), logits)
+    torch.cuda.synchronize()
+    got = logits.cpu().numpy()
+    ref64 = synth.bits_to_f64(synth.bits(w)) @ synth.bits_to_f64(synth.bits(xl))
+    assert_close_to_oracle(got, ref, f"lmhead V={V} H={H}")
+    # fp32 in, fp32 out: far tighter than the bf16 bar in practice
+    assert np.abs(got - ref64).max() <= 1e-5 * np.abs(ref64).max() + 1e-7
+    assert int(np.argmax(got)) == int(np.argmax(ref64)) or np.sort(ref64)[-1] - np.sort(ref64)[-2] < 1e-5
+
+
+def test_last_token_branch_matches_oracle():
+    """Algorithm 1 if-branch: last row -> MLP (an S=1 call) -> LM head."""
+    dev = _dev()
+    wl = synth.WORKLOADS["tiny"]
+    x, wg, wu, wd = synth.mlp_inputs(wl)
+    _, wlm = synth.lmhead_inputs(wl)
+    o_ref, l_ref = oracle.last_token(*(synth.bits(t) for t in (x, wg, wu, wd, wlm)))
+    xd, wgd, wud, wdd, wlmd = (t.to(dev) for t in (x, wg, wu, wd, wlm))
+    o_last, _ = run_mlp(xd[-1:].contiguous(), wgd, wud, wdd, 0)
+    assert_close_to_oracle(_f32(o_last)[0], o_ref, "last-token MLP")
+    logits = torch.empty((wl.V,), dtype=torch.float32, device=dev)
+    binding.mom_lmhead_last(o_last[0], wlmd, logits)
+    torch.cuda.synchronize()
+    # the oracle's head takes the oracle's bf16(O_last); the GPU's O_last may differ by a bf16 ulp
+    assert_close_to_oracle(logits.cpu().numpy(), l_ref, "last-token logits")
+    l_own = oracle.lmhead(synth.bits(o_last[0]), synth.bits(wlm))
+    assert np.abs(logits.cpu().numpy() - l_own).max() <= 1e-5 * np.abs(l_own).max()
+
+
+# ------------------------------------------------------------------ KV offload
+
+def test_kv_offload_is_byte_exact_and_ordered():
+    dev = _dev()
+    wl = synth.Workload("kv", S=4096, H=32, I=32, mini_seq=0, kv_heads=8, seed=4)
+    main = torch.cuda.current_stream()
+    side = torch.cuda.Stream()
+    order, done = torch.cuda.Event(), torch.cuda.Event()
+    order.record(main); done.record(main)                 # materialise the event handles
+    k, v = synth.kv_inputs(wl, device=dev)                # produced on the main stream
+    host = torch.empty(2 * k.numel(), dtype=torch.bfloat16).pin_memory()
+    host.zero_()
+    binding.mom_kv_offload(k, v, host, side, producer_stream=main, order_event=order, done_event=done)
+    done.synchronize()
+    n = k.numel()
+    assert np.array_equal(synth.bits(host[:n]), synth.bits(k).ravel())
+    assert np.array_equal(synth.bits(host[n:]), synth.bits(v).ravel())
+
+
+def test_kv_offload_overlaps_mlp_and_results_stay_exact():
+    dev = _dev()
+    wl = synth.Workload("kvmlp", S=8192, H=1024, I=4096, mini_seq=2048, kv_heads=8, seed=6)
+    x, wg, wu, wd = synth.mlp_inputs(wl, device=dev)
+    k, v = synth.kv_inputs(wl, device=dev)
+    alone, _ = run_mlp(x, wg, wu, wd, wl.mini_seq)
+    main = torch.cuda.current_stream()
+    side = torch.cuda.Stream()
+    order, done = torch.cuda.Event(), torch.cuda.Event()
+    order.record(main); done.record(main)
+    host = torch.empty(2 * k.numel(), dtype=torch.bfloat16).pin_memory()
+    out = torch.empty_like(x)
+    ws = torch.empty(binding.mom_mlp_workspace_bytes(wl.S, wl.H, wl.I, wl.mini_seq), dtype=torch.uint8, device=dev)
+    torch.cuda.synchronize()
+    binding.mom_kv_offload(k, v, host, side, producer_stream=main, order_event=order, done_event=done)
+    binding.mom_mlp_prefill(x, wg, wu, wd, wl.mini_seq, out, ws, stream=main)
+    done.synchronize(); torch.cuda.synchronize()
+    assert bits_equal(out, alone)
+    n = k.numel()
+    assert torch.equal(host[:n].view(torch.int16), k.cpu().view(torch.int16).ravel())
+    assert torch.equal(host[n:].view(torch.int16), v.cpu().view(torch.int16).ravel())
+
+
+# ------------------------------------------------------------------ full-size workloads, sampled rows
+
+def _full_size_case(name, sweep=(), check_unchunked=True):
+    dev = _dev()
+    wl = synth.WORKLOADS[name]
+    x, wg, wu, wd = synth.mlp_inputs(wl, device=dev)
+    out, nbytes = run_mlp(x, wg, wu, wd, wl.mini_seq)
+    assert nbytes == wl.mini_seq * wl.I * 2
+    rows = synth.parity_rows(wl.S, wl.mini_seq, n_random=96, seed=wl.seed)
+    rows_t = torch.from_numpy(rows).to(dev)
+    ref = oracle.mlp_rows(synth.bits(x[rows_t]), synth.bits(wg), synth.bits(wu), synth.bits(wd))
+    assert_close_to_oracle(_f32(out[rows_t]), ref, f"{name} sampled rows")
+    if check_unchunked:
+        full, nfull = run_mlp(x, wg, wu, wd, 0)
+        assert nfull == wl.S * wl.I * 2
+        assert bits_equal(out, full), f"{name}: mini-seq != full-sequence"
+        del full
+    for C in sweep:
+        o2, nb = run_mlp(x, wg, wu, wd, C)
+        assert nb == C * wl.I * 2
+        assert bits_equal(o2, out), f"{name}: C={C}"
+    return wl, out
+
+
+def test_llama3_8b_32k_full_size():
+    wl, out = _full_size_case("llama3_8b_32k", sweep=(1024, 2048, 8192))
+    # ragged sequence length at the same shape: 32768 - 77 rows, chunk 4096 vs full
+    dev = _dev()
+    x, wg, wu, wd = synth.mlp_inputs(wl, device=dev, S=wl.S - 77)
+    a, _ = run_mlp(x, wg, wu, wd, wl.mini_seq)
+    b, _ = run_mlp(x, wg, wu, wd, 0)
+    assert bits_equal(a, b)
+    assert bits_equal(a, out[: wl.S - 77].contiguous())     # same seed, same leading rows
+
+
+def test_llama3_8b_128k_full_size_with_offload_and_lmhead():
+    dev = _dev()
+    wl, out = _full_size_case("llama3_8b_128k", check_unchunked=True)
+    # KV offload of this layer's K,V [S,8,128] under the MLP
+    k, v = synth.kv_inputs(wl, device=dev)
+    host = torch.empty(2 * k.numel(), dtype=torch.bfloat16).pin_memory()
+    main, side = torch.cuda.current_stream(), torch.cuda.Stream()
+    order, done = torch.cuda.Event(), torch.cuda.Event()
+    order.record(main); done.record(main)
+    x, wg, wu, wd = synth.mlp_inputs(wl, device=dev)
+    out2 = torch.empty_like(x)
+    ws = torch.empty(binding.mom_mlp_workspace_bytes(wl.S, wl.H, wl.I, wl.mini_seq), dtype=torch.uint8, device=dev)
+    torch.cuda.synchronize()
+    binding.mom_kv_offload(k, v, host, side, producer_stream=main, order_event=order, done_event=done)
+    binding.mom_mlp_prefill(x, wg, wu, wd, wl.mini_seq, out2, ws)
+    done.synchronize(); torch.cuda.synchronize()
+    assert bits_equal(out2, out)
+    n = k.numel()
+    assert torch.equal(host[:n].view(torch.int16), k.cpu().view(torch.int16).ravel())
+    assert torch.equal(host[n:].view(torch.int16), v.cpu().view(torch.int16).ravel())
+    # last-token LM head, V = 128256, full V against the oracle
+    xl, wlm = synth.lmhead_inputs(wl, device=dev)
+    logits = torch.empty((wl.V,), dtype=torch.float32, device=dev)
+    binding.mom_lmhead_last(xl, wlm, logits)
+    torch.cuda.synchronize()
+    assert_close_to_oracle(logits.cpu().numpy(), oracle.lmhead(synth.bits(xl), synth.bits(wlm)), "lm head 128256")
+
+
+def test_qwen25_7b_256k_full_size():
+    dev = _dev()
+    wl, _ = _full_size_case("qwen25_7b_256k", check_unchunked=True)
+    xl, wlm = synth.lmhead_inputs(wl, device=dev)
+    logits = torch.empty((wl.V,), dtype=torch.float32, device=dev)
+    binding.mom_lmhead_last(xl, wlm, logits)
+    torch.cuda.synchronize()
+    assert_close_to_oracle(logits.cpu().numpy(), oracle.lmhead(synth.bits(xl), synth.bits(wlm)), "lm head 152064")
+
+
+def test_mistral_7b_448k_full_size():
+    _full_size_case("mistral_7b_448k", check_unchunked=True)
