@@ -29,6 +29,8 @@ def parse():
     p.add_argument("--workload", default="llama3_8b_32k")
     p.add_argument("--mini-seq", type=int, default=None, help="override the workload's mini_seq")
     p.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample; 0 skips")
+    p.add_argument("--calib", action="store_true",
+                   help="also run a plain 1 GiB elementwise copy kernel (known HBM bytes) to scale profiler counters")
     p.add_argument("--extras", action="store_true", help="also time the LM head, the KV offload overlap and a mini_seq sweep")
     return p.parse_args()
 
@@ -143,6 +145,15 @@ def main():
                      "down_kernel": {"achieved": round(dn_tflops, 2), "avg_launch_ms": round(t_dn * 1e3, 4),
                                      "frac": round(dn_tflops / BF16_MFMA_PEAK_TFLOPS, 4)}},
     }
+
+    if args.calib:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)       # 1 GiB read + 1 GiB written per launch
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.mul(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        result["calib_copy_bytes_each_way"] = src.numel() * 4
+        del src, dst
 
     if args.extras:
         result["extras"] = extras(args, binding, synth, torch, wl, tensors, out, dev)
