@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "mom.h"
 #include "mom_gemm.hip.inc"
 #include "mom_gemv.hip.inc"
