@@ -19,6 +19,9 @@ if ROOT not in sys.path:
 
 BF16_MFMA_PEAK_TFLOPS = 2500.0      # MI355X dense bf16 matrix peak (published figure)
 HBM_PEAK_GBPS = 8000.0
+# HBM-side bytes per launch of the gate/up kernel on the default workload, from rocprofv3 FETCH_SIZE + WRITE_SIZE
+# scaled by a 1 GiB copy kernel (profiles/gemm_kernels_llama3_8b_32k_counters.txt); not measured live.
+GATEUP_TRAFFIC_BYTES = {("llama3_8b_32k", 4096): 1.527e9}
 
 
 def parse():
@@ -75,13 +78,16 @@ def cpu_baseline(wl, tensors, synth, target_s):
     threads = oracle.num_threads()
     wgb, wub, wdb = synth.bits(wg), synth.bits(wu), synth.bits(wd)
     flop_row = 6.0 * wl.H * wl.I
-    probe = threads
-    xb = synth.bits(x[:probe])
-    t0 = time.perf_counter()
-    oracle.mlp_rows(xb, wgb, wub, wdb)
-    t_probe = time.perf_counter() - t0
-    rows = int(max(threads, min(4096, (target_s / max(t_probe, 1e-3)) * probe)))
-    rows -= rows % threads
+    # two probes separate the fixed cost (widening the weights) from the per-row cost
+    def run(n):
+        xb = synth.bits(x[:n])
+        t0 = time.perf_counter()
+        oracle.mlp_rows(xb, wgb, wub, wdb)
+        return time.perf_counter() - t0
+    t_a, t_b = run(threads), run(3 * threads)
+    per_batch = max((t_b - t_a) / 2.0, 1e-3)            # seconds per `threads` rows
+    fixed = max(t_a - per_batch, 0.0)
+    rows = int(max(1, min(512, (target_s - fixed) / per_batch))) * threads
     xb = synth.bits(x[:rows])
     t0 = time.perf_counter()
     oracle.mlp_rows(xb, wgb, wub, wdb)
@@ -140,7 +146,8 @@ def main():
         "workspace_bytes": ws_bytes, "unchunked_workspace_bytes": S * I * 2,
         "roofline": {"bound": "mfma", "kernel": "gemm_kernel<EPI_GATEUP> (gate/up GEMM + SiLU*up epilogue)",
                      "achieved": round(gu_tflops, 2), "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(gu_tflops / BF16_MFMA_PEAK_TFLOPS, 4), "traffic": None,
+                     "frac": round(gu_tflops / BF16_MFMA_PEAK_TFLOPS, 4),
+                     "traffic": GATEUP_TRAFFIC_BYTES.get((wl.name, C)),
                      "avg_launch_ms": round(t_gu * 1e3, 4), "flop_per_launch": 4.0 * rows_per_launch * H * I,
                      "down_kernel": {"achieved": round(dn_tflops, 2), "avg_launch_ms": round(t_dn * 1e3, 4),
                                      "frac": round(dn_tflops / BF16_MFMA_PEAK_TFLOPS, 4)}},

@@ -55,7 +55,7 @@ hipError_t launch_gemm(const unsigned short* X, const unsigned short* W0, const 
     const int tile_n = (EPI == momk::EPI_GATEUP) ? momk::kBW / 2 : momk::kBW;
     a.tiles_m = (M + momk::kBM - 1) / momk::kBM;
     a.tiles_n = (N + tile_n - 1) / tile_n;
-    a.group_m = MOM_GROUP_M;
+    a.group_m = momk::kGroupM;
     const int64_t tiles = (int64_t)a.tiles_m * a.tiles_n;
     a.tiles_per_xcd = (int)((tiles + 7) / 8);
     dim3 grid((unsigned)(a.tiles_per_xcd * 8)), block(momk::kThreads);
