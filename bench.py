@@ -202,6 +202,31 @@ def extras(args, binding, synth, torch, wl, tensors, out, dev):
     ex["lmhead"] = {"V": lm.V, "H": H, "us": round(t * 1e6, 2), "GBps": round(nbytes / t / 1e9, 1),
                     "frac_hbm_peak": round(nbytes / t / 1e9 / HBM_PEAK_GBPS, 4)}
     del wlm
+    # last-token MLP (two matrix-vector passes) against the same call through the matrix-core path
+    x, wg, wu, wd = tensors
+    o1 = torch.empty((H,), dtype=torch.bfloat16, device=dev)
+    wsl = torch.empty(I * 2, dtype=torch.uint8, device=dev)
+    for _ in range(3):
+        binding.mom_mlp_last(x[-1], wg, wu, wd, o1, wsl)
+    e0.record(st)
+    for _ in range(reps):
+        binding.mom_mlp_last(x[-1], wg, wu, wd, o1, wsl)
+    e1.record(st)
+    torch.cuda.synchronize()
+    t = e0.elapsed_time(e1) * 1e-3 / reps
+    xl1 = x[-1:].contiguous(); o2 = torch.empty((1, H), dtype=torch.bfloat16, device=dev)
+    for _ in range(2):
+        binding.mom_mlp_prefill(xl1, wg, wu, wd, 0, o2, wsl)
+    e0.record(st)
+    for _ in range(reps):
+        binding.mom_mlp_prefill(xl1, wg, wu, wd, 0, o2, wsl)
+    e1.record(st)
+    torch.cuda.synchronize()
+    t2 = e0.elapsed_time(e1) * 1e-3 / reps
+    mb = 6.0 * H * I + 4.0 * I + 4.0 * H
+    ex["last_token_mlp"] = {"H": H, "I": I, "us": round(t * 1e6, 2), "GBps": round(mb / t / 1e9, 1),
+                            "frac_hbm_peak": round(mb / t / 1e9 / HBM_PEAK_GBPS, 4),
+                            "us_through_gemm_kernels_S1": round(t2 * 1e6, 2)}
     # KV offload [S,8,128] x2 under the MLP
     kvw = synth.Workload("kv", S=S, H=H, I=I, mini_seq=wl.mini_seq, kv_heads=8)
     k, v = synth.kv_inputs(kvw, device=dev)

@@ -102,10 +102,26 @@ int mom_mlp_prefill_events(const void *x, const void *W_gate, const void *W_up, 
  *     logits[v] = sum_k x_last[k] * W_lm[v,k]
  *   x_last [H] bf16 in,  W_lm [V,H] bf16 in,  logits [V] fp32 out.
  * fp32 accumulation, fp32 result (no rounding before an argmax / softmax).
- * H must be a positive multiple of 32 and at most 16384; V = 0 is a no-op.
+ * H must be a positive multiple of 32 and at most 32768; V = 0 is a no-op.
  */
 int mom_lmhead_last(const void *x_last, const void *W_lm, int64_t V, float *logits,
                     int64_t H, void *stream);
+
+/*
+ * Last-token MLP (Algorithm 1, if-branch: O_last = MLP(A_last)), tuned for one token: two
+ * bandwidth-bound matrix-vector passes that stream each weight exactly once,
+ *     h = silu(x_last W_gate^T) .* (x_last W_up^T)   [I] bf16 -> workspace
+ *     out_last = h W_down^T                          [H] bf16
+ *   x_last [H] bf16 in; W_gate, W_up [I,H], W_down [H,I] bf16 in; out_last [H] bf16 out;
+ *   workspace: at least I*2 bytes of scratch.
+ * Same arithmetic contract as mom_mlp_prefill (fp32 accumulation, fp32 SiLU and product, one
+ * rounding to bf16 per projection), but the summation order differs from the matrix-core path, so
+ * the result agrees with mom_mlp_prefill(S=1) to rounding, not bit for bit.
+ * H and I must be positive multiples of 32 and at most 32768.
+ */
+int mom_mlp_last(const void *x_last, const void *W_gate, const void *W_up, const void *W_down,
+                 int64_t H, int64_t I, void *out_last, void *workspace, size_t workspace_bytes,
+                 void *stream);
 
 /*
  * KV-cache offload of one layer (Algorithm 1 "offload"; Section 3.2): byte-exact
@@ -125,6 +141,15 @@ int mom_lmhead_last(const void *x_last, const void *W_lm, int64_t V, float *logi
 int mom_kv_offload(const void *k, const void *v, void *pinned_host, void *stream,
                    size_t bytes_each, void *producer_stream, void *order_event,
                    void *done_event);
+
+/*
+ * KV-cache reload before decode (Algorithm 1, if-branch: "transfer offloaded cache back to GPU";
+ * Section 3.2): the mirror of mom_kv_offload.  Asynchronous copy of bytes_each bytes from
+ * `pinned_host` (host, page-locked; k at offset 0, v at offset bytes_each) into device k and v
+ * on `stream`; `done_event`, if not NULL, is recorded after both copies.
+ */
+int mom_kv_reload(const void *pinned_host, void *k, void *v, void *stream, size_t bytes_each,
+                  void *done_event);
 
 #ifdef __cplusplus
 }

@@ -14,7 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmom.so")
 
 SYMBOLS = ("mom_status_string", "mom_mlp_workspace_bytes", "mom_mlp_prefill", "mom_mlp_prefill_events",
-           "mom_lmhead_last", "mom_kv_offload")
+           "mom_lmhead_last", "mom_mlp_last", "mom_kv_offload", "mom_kv_reload")
 
 MOM_OK, MOM_ERR_NULL, MOM_ERR_SHAPE, MOM_ERR_ALIGN, MOM_ERR_ALIAS, MOM_ERR_WORKSPACE, MOM_ERR_HIP = range(7)
 
@@ -49,6 +49,10 @@ def lib():
         L.mom_lmhead_last.argtypes = [vp, vp, i64, vp, i64, vp]
         L.mom_kv_offload.restype = ctypes.c_int
         L.mom_kv_offload.argtypes = [vp, vp, vp, vp, sz, vp, vp, vp]
+        L.mom_mlp_last.restype = ctypes.c_int
+        L.mom_mlp_last.argtypes = [vp, vp, vp, vp, i64, i64, vp, vp, sz, vp]
+        L.mom_kv_reload.restype = ctypes.c_int
+        L.mom_kv_reload.argtypes = [vp, vp, vp, vp, sz, vp]
         _lib = L
     return _lib
 
@@ -121,4 +125,26 @@ def mom_kv_offload(k, v, pinned_host, stream, producer_stream=None, order_event=
                               None if done_event is None else ctypes.c_void_p(done_event.cuda_event))
     if rc != MOM_OK:
         raise MomError(rc, "mom_kv_offload")
+    return rc
+
+
+def mom_mlp_last(x_last, W_gate, W_up, W_down, out_last, workspace, stream=None, check=True):
+    """x_last [H], W_gate/W_up [I,H], W_down [H,I], out_last [H] bf16 device tensors; workspace >= I*2 bytes."""
+    I, H = W_gate.shape
+    rc = lib().mom_mlp_last(_ptr(x_last), _ptr(W_gate), _ptr(W_up), _ptr(W_down), H, I, _ptr(out_last),
+                            _ptr(workspace), _nbytes(workspace), _stream(stream))
+    if check and rc != MOM_OK:
+        raise MomError(rc, "mom_mlp_last")
+    return rc
+
+
+def mom_kv_reload(pinned_host, k, v, stream, done_event=None):
+    """Copy k then v back from the pinned host tensor into the device tensors on `stream`."""
+    nb = _nbytes(k)
+    if _nbytes(v) != nb or _nbytes(pinned_host) < 2 * nb:
+        raise ValueError("k and v must have equal byte size and pinned_host must hold both")
+    rc = lib().mom_kv_reload(_ptr(pinned_host), _ptr(k), _ptr(v), _stream(stream), nb,
+                             None if done_event is None else ctypes.c_void_p(done_event.cuda_event))
+    if rc != MOM_OK:
+        raise MomError(rc, "mom_kv_reload")
     return rc

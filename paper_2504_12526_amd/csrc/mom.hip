@@ -63,6 +63,18 @@ hipError_t launch_gemm(const unsigned short* X, const unsigned short* W0, const 
     return hipGetLastError();
 }
 
+template <int MODE>
+hipError_t launch_gemv(const unsigned short* x, const unsigned short* Wa, const unsigned short* Wb, void* y,
+                       int64_t R, int64_t K, hipStream_t st) {
+    const int rows_per_block = momk::kGemvWaves * (MODE == momk::MODE_GATEUP ? momk::kGemvStreams / 2 : (MODE == momk::MODE_DOWN ? 1 : momk::kGemvStreams));
+    int64_t blocks = (R + rows_per_block - 1) / rows_per_block;
+    const int64_t max_blocks = 256 * 8;          // a few resident workgroups per CU; each loops over rows
+    if (blocks > max_blocks) blocks = max_blocks;
+    hipLaunchKernelGGL(momk::gemv_kernel<MODE>, dim3((unsigned)blocks), dim3(momk::kGemvWaves * 64),
+                       (size_t)K * 2, st, x, Wa, Wb, y, (int)R, (int)K);
+    return hipGetLastError();
+}
+
 int mlp_driver(const void* x, const void* wg, const void* wu, const void* wd, int64_t S, int64_t H,
                int64_t I, int64_t mini_seq, void* out, void* ws, size_t ws_bytes, void* stream,
                void** events, int64_t n_events) {
@@ -133,22 +145,44 @@ int mom_mlp_prefill_events(const void* x, const void* W_gate, const void* W_up, 
 }
 
 int mom_lmhead_last(const void* x_last, const void* W_lm, int64_t V, float* logits, int64_t H, void* stream) {
-    if (V < 0 || H <= 0 || (H % 32) != 0 || H > momk::kGemvMaxH || V > (int64_t)0x7fffff00) return MOM_ERR_SHAPE;
+    if (V < 0 || H <= 0 || (H % 32) != 0 || H > momk::kGemvMaxK || V > (int64_t)0x7fffff00) return MOM_ERR_SHAPE;
     if (V == 0) return MOM_OK;
     if (!x_last || !W_lm || !logits) return MOM_ERR_NULL;
     if (!aligned16(x_last) || !aligned16(W_lm) || !aligned16(logits)) return MOM_ERR_ALIGN;
     if (overlaps(logits, (size_t)V * 4, x_last, (size_t)H * 2) ||
         overlaps(logits, (size_t)V * 4, W_lm, (size_t)V * H * 2))
         return MOM_ERR_ALIAS;
+    return launch_gemv<momk::MODE_LOGITS>(static_cast<const unsigned short*>(x_last),
+                                          static_cast<const unsigned short*>(W_lm), nullptr, logits, V, H,
+                                          static_cast<hipStream_t>(stream)) == hipSuccess ? MOM_OK : MOM_ERR_HIP;
+}
+
+int mom_mlp_last(const void* x_last, const void* W_gate, const void* W_up, const void* W_down, int64_t H,
+                 int64_t I, void* out_last, void* workspace, size_t workspace_bytes, void* stream) {
+    if (H <= 0 || I <= 0 || (H % 32) != 0 || (I % 32) != 0 || H > momk::kGemvMaxK || I > momk::kGemvMaxK)
+        return MOM_ERR_SHAPE;
+    if (!x_last || !W_gate || !W_up || !W_down || !out_last || !workspace) return MOM_ERR_NULL;
+    if (!aligned16(x_last) || !aligned16(W_gate) || !aligned16(W_up) || !aligned16(W_down) ||
+        !aligned16(out_last) || !aligned16(workspace))
+        return MOM_ERR_ALIGN;
+    const size_t need = (size_t)I * 2, hb = (size_t)H * 2, wb = (size_t)H * I * 2;
+    if (workspace_bytes < need) return MOM_ERR_WORKSPACE;
+    const void* ins[4] = {x_last, W_gate, W_up, W_down};
+    const size_t inb[4] = {hb, wb, wb, wb};
+    for (int i = 0; i < 4; ++i)
+        if (overlaps(out_last, hb, ins[i], inb[i]) || overlaps(workspace, need, ins[i], inb[i])) return MOM_ERR_ALIAS;
+    if (overlaps(out_last, hb, workspace, need)) return MOM_ERR_ALIAS;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const int rows_per_block = momk::kGemvWaves * momk::kGemvRowsPerWave;
-    int64_t blocks = (V + rows_per_block - 1) / rows_per_block;
-    const int64_t max_blocks = 256 * 8;          // a few resident workgroups per CU; each loops over rows
-    if (blocks > max_blocks) blocks = max_blocks;
-    hipLaunchKernelGGL(momk::lmhead_gemv_kernel, dim3((unsigned)blocks), dim3(momk::kGemvWaves * 64), 0, st,
-                       static_cast<const unsigned short*>(x_last), static_cast<const unsigned short*>(W_lm),
-                       logits, (int)V, (int)H);
-    return hipGetLastError() == hipSuccess ? MOM_OK : MOM_ERR_HIP;
+    // h = silu(x Wg^T) .* (x Wu^T)  ->  workspace [I] bf16 ;  out = h Wd^T -> [H] bf16
+    if (launch_gemv<momk::MODE_GATEUP>(static_cast<const unsigned short*>(x_last),
+                                       static_cast<const unsigned short*>(W_gate),
+                                       static_cast<const unsigned short*>(W_up), workspace, I, H, st) != hipSuccess)
+        return MOM_ERR_HIP;
+    if (launch_gemv<momk::MODE_DOWN>(static_cast<const unsigned short*>(workspace),
+                                     static_cast<const unsigned short*>(W_down), nullptr, out_last, H, I,
+                                     st) != hipSuccess)
+        return MOM_ERR_HIP;
+    return MOM_OK;
 }
 
 int mom_kv_offload(const void* k, const void* v, void* pinned_host, void* stream, size_t bytes_each,
@@ -165,6 +199,19 @@ int mom_kv_offload(const void* k, const void* v, void* pinned_host, void* stream
         unsigned char* dst = static_cast<unsigned char*>(pinned_host);
         if (hipMemcpyAsync(dst, k, bytes_each, hipMemcpyDeviceToHost, st) != hipSuccess) return MOM_ERR_HIP;
         if (hipMemcpyAsync(dst + bytes_each, v, bytes_each, hipMemcpyDeviceToHost, st) != hipSuccess)
+            return MOM_ERR_HIP;
+    }
+    if (done_event && hipEventRecord(static_cast<hipEvent_t>(done_event), st) != hipSuccess) return MOM_ERR_HIP;
+    return MOM_OK;
+}
+
+int mom_kv_reload(const void* pinned_host, void* k, void* v, void* stream, size_t bytes_each, void* done_event) {
+    if (bytes_each != 0 && (!k || !v || !pinned_host)) return MOM_ERR_NULL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (bytes_each != 0) {
+        const unsigned char* src = static_cast<const unsigned char*>(pinned_host);
+        if (hipMemcpyAsync(k, src, bytes_each, hipMemcpyHostToDevice, st) != hipSuccess) return MOM_ERR_HIP;
+        if (hipMemcpyAsync(v, src + bytes_each, bytes_each, hipMemcpyHostToDevice, st) != hipSuccess)
             return MOM_ERR_HIP;
     }
     if (done_event && hipEventRecord(static_cast<hipEvent_t>(done_event), st) != hipSuccess) return MOM_ERR_HIP;

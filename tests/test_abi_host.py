@@ -72,11 +72,22 @@ def test_lmhead_and_offload_argument_validation():
     L = binding.lib()
     assert L.mom_lmhead_last(vp(0x1000), vp(0x2000), 16, vp(0x900000), 40, None) == binding.MOM_ERR_SHAPE
     assert L.mom_lmhead_last(vp(0x1000), vp(0x2000), -1, vp(0x900000), 64, None) == binding.MOM_ERR_SHAPE
-    assert L.mom_lmhead_last(vp(0x1000), vp(0x2000), 16, vp(0x900000), 32768, None) == binding.MOM_ERR_SHAPE
+    assert L.mom_lmhead_last(vp(0x1000), vp(0x2000), 16, vp(0x900000), 65536, None) == binding.MOM_ERR_SHAPE
     assert L.mom_lmhead_last(None, vp(0x2000), 16, vp(0x900000), 64, None) == binding.MOM_ERR_NULL
     assert L.mom_lmhead_last(vp(0x1002), vp(0x2000), 16, vp(0x900000), 64, None) == binding.MOM_ERR_ALIGN
     assert L.mom_lmhead_last(vp(0x1000), vp(0x2000), 16, vp(0x2010), 64, None) == binding.MOM_ERR_ALIAS
     assert L.mom_lmhead_last(None, None, 0, None, 64, None) == binding.MOM_OK
+    # last-token MLP: x [64], weights [96,64] / [64,96] at fake addresses
+    def last(x=0x1000, wg=0x200000, wu=0x300000, wd=0x400000, H=64, I=96, out=0x500000, ws=0x600000, wsb=192):
+        return L.mom_mlp_last(vp(x), vp(wg), vp(wu), vp(wd), H, I, vp(out), vp(ws), wsb, None)
+    assert last(H=40) == binding.MOM_ERR_SHAPE
+    assert last(I=65536) == binding.MOM_ERR_SHAPE
+    assert last(wd=0) == binding.MOM_ERR_NULL
+    assert last(out=0x500008) == binding.MOM_ERR_ALIGN
+    assert last(wsb=191) == binding.MOM_ERR_WORKSPACE
+    assert last(out=0x200010) == binding.MOM_ERR_ALIAS
+    assert last(ws=0x500000 + 64) == binding.MOM_ERR_ALIAS
+    assert L.mom_kv_reload(None, vp(0x10), vp(0x20), None, 16, None) == binding.MOM_ERR_NULL
     assert L.mom_kv_offload(None, vp(0x10), vp(0x20), None, 16, None, None, None) == binding.MOM_ERR_NULL
     assert L.mom_kv_offload(vp(0x10), vp(0x20), vp(0x30), None, 16, vp(0x1), None, None) == binding.MOM_ERR_NULL
 

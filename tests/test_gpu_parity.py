@@ -200,6 +200,47 @@ def test_last_token_branch_matches_oracle():
     assert np.abs(logits.cpu().numpy() - l_own).max() <= 1e-5 * np.abs(l_own).max()
 
 
+@pytest.mark.parametrize("H,I", [(256, 1024), (4096, 14336), (3584, 18944), (96, 160), (32, 32)])
+def test_last_token_mlp_gemv_matches_oracle(H, I):
+    """mom_mlp_last (one-token matrix-vector path) against the oracle and against the matrix-core path."""
+    dev = _dev()
+    wl = synth.Workload("last", S=3, H=H, I=I, mini_seq=0, seed=H % 89)
+    x, wg, wu, wd = synth.mlp_inputs(wl, device=dev if H * I > 1 << 22 else "cpu")
+    x, wg, wu, wd = (t.to(dev) for t in (x, wg, wu, wd))
+    last = torch.tensor([wl.S - 1])
+    ref = oracle.mlp_rows(synth.bits(x), synth.bits(wg), synth.bits(wu), synth.bits(wd), rows=last.numpy())[0]
+    out = torch.full((H,), float("nan"), dtype=torch.bfloat16, device=dev)
+    ws = torch.empty(I * 2, dtype=torch.uint8, device=dev)
+    binding.mom_mlp_last(x[-1], wg, wu, wd, out, ws)
+    torch.cuda.synchronize()
+    assert_close_to_oracle(_f32(out), ref, f"mom_mlp_last H={H} I={I}")
+    via_gemm, _ = run_mlp(x[-1:].contiguous(), wg, wu, wd, 0)
+    assert_close_to_oracle(_f32(out), _f32(via_gemm)[0], "gemv path vs matrix-core path")
+    # the intermediate it left in the workspace is h = silu(g)*u rounded once to bf16
+    xf = synth.bits_to_f64(synth.bits(x[-1])); g = synth.bits_to_f64(synth.bits(wg)) @ xf
+    u = synth.bits_to_f64(synth.bits(wu)) @ xf
+    h_ref = g / (1 + np.exp(-g)) * u
+    assert_close_to_oracle(_f32(ws.view(torch.bfloat16)), h_ref.astype(np.float32), "intermediate h")
+
+
+def test_last_token_branch_end_to_end_gemv():
+    """Algorithm 1 if-branch with the one-token kernels only: A_last -> mom_mlp_last -> mom_lmhead_last."""
+    dev = _dev()
+    wl = synth.WORKLOADS["tiny"]
+    x, wg, wu, wd = synth.mlp_inputs(wl)
+    _, wlm = synth.lmhead_inputs(wl)
+    o_ref, l_ref = oracle.last_token(*(synth.bits(t) for t in (x, wg, wu, wd, wlm)))
+    xd, wgd, wud, wdd, wlmd = (t.to(dev) for t in (x, wg, wu, wd, wlm))
+    o_last = torch.empty((wl.H,), dtype=torch.bfloat16, device=dev)
+    ws = torch.empty(wl.I * 2, dtype=torch.uint8, device=dev)
+    logits = torch.empty((wl.V,), dtype=torch.float32, device=dev)
+    binding.mom_mlp_last(xd[-1], wgd, wud, wdd, o_last, ws)
+    binding.mom_lmhead_last(o_last, wlmd, logits)
+    torch.cuda.synchronize()
+    assert_close_to_oracle(_f32(o_last), o_ref, "O_last")
+    assert_close_to_oracle(logits.cpu().numpy(), l_ref, "logits")
+
+
 # ------------------------------------------------------------------ KV offload
 
 def test_kv_offload_is_byte_exact_and_ordered():
@@ -217,6 +258,25 @@ def test_kv_offload_is_byte_exact_and_ordered():
     n = k.numel()
     assert np.array_equal(synth.bits(host[:n]), synth.bits(k).ravel())
     assert np.array_equal(synth.bits(host[n:]), synth.bits(v).ravel())
+
+
+def test_kv_reload_round_trip():
+    """Offload then reload (Algorithm 1: cache back to the GPU before decode) returns the same bytes."""
+    dev = _dev()
+    wl = synth.Workload("kvr", S=2048, H=32, I=32, mini_seq=0, kv_heads=8, seed=9)
+    k, v = synth.kv_inputs(wl, device=dev)
+    host = torch.empty(2 * k.numel(), dtype=torch.bfloat16).pin_memory()
+    main, side = torch.cuda.current_stream(), torch.cuda.Stream()
+    order, done, back = torch.cuda.Event(), torch.cuda.Event(), torch.cuda.Event()
+    for e in (order, done, back):
+        e.record(main)
+    binding.mom_kv_offload(k, v, host, side, producer_stream=main, order_event=order, done_event=done)
+    done.synchronize()
+    k2, v2 = torch.zeros_like(k), torch.zeros_like(v)
+    torch.cuda.synchronize()
+    binding.mom_kv_reload(host, k2, v2, side, done_event=back)
+    back.synchronize()
+    assert bits_equal(k2, k) and bits_equal(v2, v)
 
 
 def test_kv_offload_overlaps_mlp_and_results_stay_exact():
