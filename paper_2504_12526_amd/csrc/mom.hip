@@ -9,6 +9,7 @@
 
 #include "mom.h"
 #include "mom_gemm.hip.inc"
+#include "mom_gemm4.hip.inc"
 #include "mom_gemv.hip.inc"
 
 namespace {
@@ -58,8 +59,17 @@ hipError_t launch_gemm(const unsigned short* X, const unsigned short* W0, const 
     a.group_m = momk::kGroupM;
     const int64_t tiles = (int64_t)a.tiles_m * a.tiles_n;
     a.tiles_per_xcd = (int)((tiles + 7) / 8);
-    dim3 grid((unsigned)(a.tiles_per_xcd * 8)), block(momk::kThreads);
-    hipLaunchKernelGGL(momk::gemm_kernel<EPI>, grid, block, 0, st, a);
+    dim3 grid((unsigned)(a.tiles_per_xcd * 8));
+    // Both kernels give identical bits; the four-wavefront one needs whole 64-wide K stages.  The
+    // choice depends on K alone, never on the number of rows, so every mini-sequence of a layer
+    // runs the same kernel.
+#ifndef MOM_GEMM8_ONLY
+    if (K % 64 == 0) {
+        hipLaunchKernelGGL(momk::gemm4_kernel<EPI>, grid, dim3(momk::k4Threads), 0, st, a);
+        return hipGetLastError();
+    }
+#endif
+    hipLaunchKernelGGL(momk::gemm_kernel<EPI>, grid, dim3(momk::kThreads), 0, st, a);
     return hipGetLastError();
 }
 

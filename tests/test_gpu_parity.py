@@ -73,7 +73,9 @@ def test_tiny_workload_matches_oracle_and_unchunked():
     assert bits_equal(out, full)
 
 
-@pytest.mark.parametrize("S,H,I", [(300, 96, 160), (257, 256, 288), (1, 64, 32), (513, 32, 1056), (40, 544, 96)])
+@pytest.mark.parametrize("S,H,I", [(300, 96, 160), (257, 256, 288), (1, 64, 32), (513, 32, 1056), (40, 544, 96),
+                                   # H and I multiples of 64 (the four-wavefront kernel): one stage, ring wrap-around
+                                   (257, 64, 64), (300, 128, 192), (130, 320, 448), (700, 384, 640)])
 def test_ragged_shapes_match_oracle(S, H, I):
     dev = _dev()
     wl = synth.Workload("ragged", S=S, H=H, I=I, mini_seq=0, seed=S + H + I, w_std=0.05)
