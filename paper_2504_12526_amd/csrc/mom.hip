@@ -4,6 +4,8 @@
 // last-token LM head launch and the KV offload copies.  Nothing here allocates or synchronises.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
 
 #include <type_traits>
 
@@ -47,29 +49,54 @@ int validate_mlp(const void* x, const void* wg, const void* wu, const void* wd, 
     return MOM_OK;
 }
 
+// Compute units of the current device, or 0 on error.
+int compute_units() {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+    return cus;
+}
+
 template <int EPI>
 hipError_t launch_gemm(const unsigned short* X, const unsigned short* W0, const unsigned short* W1,
                        unsigned short* O, int M, int N, int K, hipStream_t st) {
     momk::GemmArgs a;
     a.X = X; a.W0 = W0; a.W1 = W1; a.O = O;
     a.M = M; a.N = N; a.K = K;
-    const int tile_n = (EPI == momk::EPI_GATEUP) ? momk::kBW / 2 : momk::kBW;
-    a.tiles_m = (M + momk::kBM - 1) / momk::kBM;
-    a.tiles_n = (N + tile_n - 1) / tile_n;
     a.group_m = momk::kGroupM;
-    const int64_t tiles = (int64_t)a.tiles_m * a.tiles_n;
-    a.tiles_per_xcd = (int)((tiles + 7) / 8);
-    dim3 grid((unsigned)(a.tiles_per_xcd * 8));
-    // Both kernels give identical bits; the four-wavefront one needs whole 64-wide K stages.  The
-    // choice depends on K alone, never on the number of rows, so every mini-sequence of a layer
-    // runs the same kernel.
+    auto set_tiles = [&](int tile) {
+        const int tile_n = (EPI == momk::EPI_GATEUP) ? tile / 2 : tile;
+        a.tiles_m = (M + tile - 1) / tile;
+        a.tiles_n = (N + tile_n - 1) / tile_n;
+        const int64_t tiles = (int64_t)a.tiles_m * a.tiles_n;
+        a.tiles_per_xcd = (int)((tiles + 7) / 8);
+        return tiles;
+    };
+    const int64_t tiles = set_tiles(momk::kBM);
+    // All kernels give identical bits (every output element sees the same MFMA sequence over k), so
+    // the choice is free: the four-wavefront kernel needs whole 64-wide K stages, and its 128-tile
+    // form is used when 256-tiles would leave a quarter or more of the CUs without work.
 #ifndef MOM_GEMM8_ONLY
     if (K % 64 == 0) {
-        hipLaunchKernelGGL(momk::gemm4_kernel<EPI>, grid, dim3(momk::k4Threads), 0, st, a);
+        const int cus = compute_units();
+        if (cus <= 0) return hipErrorInvalidDevice;
+        // MOM_GEMM_TILE=128|256 in the environment overrides the choice (for tests, which need both
+        // forms on shapes of every size).
+        const char* force = getenv("MOM_GEMM_TILE");
+        const bool small = force && force[0] ? (strcmp(force, "128") == 0) : (tiles * 4 <= (int64_t)cus * 3);
+        if (small) {
+            set_tiles(128);
+            hipLaunchKernelGGL((momk::gemm4_kernel<EPI, 128>), dim3((unsigned)(a.tiles_per_xcd * 8)),
+                               dim3(momk::k4Threads), 0, st, a);
+        } else {
+            hipLaunchKernelGGL((momk::gemm4_kernel<EPI, 256>), dim3((unsigned)(a.tiles_per_xcd * 8)),
+                               dim3(momk::k4Threads), 0, st, a);
+        }
         return hipGetLastError();
     }
 #endif
-    hipLaunchKernelGGL(momk::gemm_kernel<EPI>, grid, dim3(momk::kThreads), 0, st, a);
+    hipLaunchKernelGGL(momk::gemm_kernel<EPI>, dim3((unsigned)(a.tiles_per_xcd * 8)), dim3(momk::kThreads), 0, st,
+                       a);
     return hipGetLastError();
 }
 
