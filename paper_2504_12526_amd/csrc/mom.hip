@@ -73,6 +73,7 @@ hipError_t launch_gemm(const unsigned short* X, const unsigned short* W0, const 
         return tiles;
     };
     const int64_t tiles = set_tiles(momk::kBM);
+    if (tiles > (int64_t)0x1fffffff) return hipErrorInvalidValue;      // tile numbers are 32-bit in the kernels
     // All kernels give identical bits (every output element sees the same MFMA sequence over k), so
     // the choice is free: the four-wavefront kernel needs whole 64-wide K stages, and its 128-tile
     // form is used when 256-tiles would leave a quarter or more of the CUs without work.
@@ -85,7 +86,7 @@ hipError_t launch_gemm(const unsigned short* X, const unsigned short* W0, const 
         const char* force = getenv("MOM_GEMM_TILE");
         const bool small = force && force[0] ? (strcmp(force, "128") == 0) : (tiles * 4 <= (int64_t)cus * 3);
         if (small) {
-            set_tiles(128);
+            if (set_tiles(128) > (int64_t)0x1fffffff) return hipErrorInvalidValue;
             hipLaunchKernelGGL((momk::gemm4_kernel<EPI, 128>), dim3((unsigned)(a.tiles_per_xcd * 8)),
                                dim3(momk::k4Threads), 0, st, a);
         } else {
