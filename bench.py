@@ -270,6 +270,44 @@ def extras(args, binding, synth, torch, wl, tensors, out, dev):
                         "mlp_slowdown": round(min(t_with) / t_mlp - 1.0, 4),
                         "kv_matches": bool(torch.equal(host[: k.numel()].view(torch.int16),
                                                        k.cpu().view(torch.int16).ravel()))}
+    # a stack of layers (Algorithm 1 per layer): layer l's K/V (2 x 128 MiB) go to the host under layer l's MLP;
+    # two device K/V buffers, buffer l%2 reused by layer l+2 only after the copy of layer l has finished
+    del k, v, host
+    L = 6
+    kvl = synth.Workload("kvl", S=65536, H=H, I=I, mini_seq=wl.mini_seq, kv_heads=8)
+    bk, bv = synth.kv_inputs(kvl, device=dev)
+    kb = [torch.empty_like(bk) for _ in range(2)]
+    vb = [torch.empty_like(bv) for _ in range(2)]
+    hosts = [torch.empty(2 * bk.numel(), dtype=torch.bfloat16).pin_memory() for _ in range(L)]
+    orders = [torch.cuda.Event() for _ in range(L)]
+    dones = [torch.cuda.Event() for _ in range(L)]
+    for e in orders + dones:
+        e.record(st)
+
+    def stack(offload):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for l in range(L):
+            b = l % 2
+            if offload and l >= 2:
+                st.wait_event(dones[l - 2])
+            torch.mul(bk, float(l + 1), out=kb[b])
+            torch.mul(bv, float(l + 1), out=vb[b])
+            if offload:
+                binding.mom_kv_offload(kb[b], vb[b], hosts[l], side, producer_stream=st, order_event=orders[l],
+                                       done_event=dones[l])
+            binding.mom_mlp_prefill(*tensors, wl.mini_seq, out, ws, stream=st)
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+
+    stack(True)                                   # maps the pinned pages
+    t_plain = min(stack(False) for _ in range(2))
+    t_off = min(stack(True) for _ in range(2))
+    last_ok = bool(torch.equal(hosts[L - 1][: bk.numel()].view(torch.int16),
+                               (bk * float(L)).cpu().view(torch.int16).ravel()))
+    ex["layer_stack"] = {"layers": L, "kv_bytes_per_layer": 2 * bk.numel() * 2,
+                         "mlp_only_ms": round(t_plain * 1e3, 3), "mlp_plus_offload_ms": round(t_off * 1e3, 3),
+                         "offload_cost": round(t_off / t_plain - 1.0, 4), "last_layer_matches": last_ok}
     return ex
 
 

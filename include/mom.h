@@ -131,11 +131,12 @@ int mom_mlp_last(const void *x_last, const void *W_gate, const void *W_up, const
  * `pinned_host` (host, page-locked, at least 2*bytes_each bytes; k at offset 0,
  * v at offset bytes_each) on `stream`, meant to be a side stream so the copy
  * runs under the MLP kernels.
- *   producer_stream  if not NULL, an event is recorded there first and `stream`
- *                    waits for it, so the copy starts after the work that
- *                    produced k and v (requires `order_event`)
- *   order_event      hipEvent_t used for that ordering; may be NULL only when
- *                    producer_stream is NULL
+ *   order_event      hipEvent_t; if not NULL it is recorded on producer_stream first and `stream`
+ *                    waits for it, so the copy starts after the work that produced k and v
+ *   producer_stream  the stream that produced k and v; NULL means the default stream (which does
+ *                    NOT order itself against a non-blocking side stream, so pass order_event
+ *                    in that case too).  Ignored when order_event is NULL; passing a non-NULL
+ *                    producer_stream without an order_event is an error (MOM_ERR_NULL)
  *   done_event       if not NULL, recorded on `stream` after both copies; the
  *                    device k/v may be reused once it has completed
  * bytes_each = 0 is a no-op (events are still recorded).

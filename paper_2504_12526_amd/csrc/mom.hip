@@ -228,7 +228,9 @@ int mom_kv_offload(const void* k, const void* v, void* pinned_host, void* stream
     if (bytes_each != 0 && (!k || !v || !pinned_host)) return MOM_ERR_NULL;
     if (producer_stream && !order_event) return MOM_ERR_NULL;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (producer_stream) {
+    if (order_event) {
+        // producer_stream may be NULL here: that is the default stream, which does not order itself
+        // against a non-blocking side stream
         hipEvent_t ev = static_cast<hipEvent_t>(order_event);
         if (hipEventRecord(ev, static_cast<hipStream_t>(producer_stream)) != hipSuccess) return MOM_ERR_HIP;
         if (hipStreamWaitEvent(st, ev, 0) != hipSuccess) return MOM_ERR_HIP;

@@ -245,21 +245,37 @@ def test_last_token_branch_end_to_end_gemv():
 
 # ------------------------------------------------------------------ KV offload
 
-def test_kv_offload_is_byte_exact_and_ordered():
+@pytest.mark.parametrize("producer", ["default_stream", "own_stream"])
+def test_kv_offload_is_byte_exact_and_ordered(producer):
+    """The copy must start after the work that produced K and V, whichever stream produced them
+    (the default stream does not order itself against a non-blocking side stream).  The producer
+    stream is kept busy first, so a copy that is not ordered runs ahead and reads the zeros."""
     dev = _dev()
-    wl = synth.Workload("kv", S=4096, H=32, I=32, mini_seq=0, kv_heads=8, seed=4)
-    main = torch.cuda.current_stream()
+    wl = synth.Workload("kv", S=8192, H=2048, I=8192, mini_seq=0, kv_heads=8, seed=4)
+    x, wg, wu, wd = synth.mlp_inputs(wl, device=dev)
+    src_k, src_v = synth.kv_inputs(wl, device=dev)
+    k, v = torch.zeros_like(src_k), torch.zeros_like(src_v)
+    out = torch.empty_like(x)
+    ws = torch.empty(binding.mom_mlp_workspace_bytes(wl.S, wl.H, wl.I, 0), dtype=torch.uint8, device=dev)
+    host = torch.empty(2 * k.numel(), dtype=torch.bfloat16).pin_memory()
+    main = torch.cuda.current_stream() if producer == "default_stream" else torch.cuda.Stream()
     side = torch.cuda.Stream()
     order, done = torch.cuda.Event(), torch.cuda.Event()
     order.record(main); done.record(main)                 # materialise the event handles
-    k, v = synth.kv_inputs(wl, device=dev)                # produced on the main stream
-    host = torch.empty(2 * k.numel(), dtype=torch.bfloat16).pin_memory()
-    host.zero_()
+    torch.cuda.synchronize()
+    # a first copy maps the pinned pages (slow); it copies the zeros
     binding.mom_kv_offload(k, v, host, side, producer_stream=main, order_event=order, done_event=done)
     done.synchronize()
+    with torch.cuda.stream(main):
+        for _ in range(24):                               # some 15 ms of work ahead of the producer
+            binding.mom_mlp_prefill(x, wg, wu, wd, 0, out, ws, stream=main)
+        k.copy_(src_k); v.copy_(src_v)                    # the producer
+        binding.mom_kv_offload(k, v, host, side, producer_stream=main, order_event=order, done_event=done)
+    done.synchronize()
     n = k.numel()
-    assert np.array_equal(synth.bits(host[:n]), synth.bits(k).ravel())
-    assert np.array_equal(synth.bits(host[n:]), synth.bits(v).ravel())
+    assert np.array_equal(synth.bits(host[:n]), synth.bits(src_k).ravel())
+    assert np.array_equal(synth.bits(host[n:]), synth.bits(src_v).ravel())
+    torch.cuda.synchronize()
 
 
 def test_kv_reload_round_trip():
@@ -302,6 +318,75 @@ def test_kv_offload_overlaps_mlp_and_results_stay_exact():
     n = k.numel()
     assert torch.equal(host[:n].view(torch.int16), k.cpu().view(torch.int16).ravel())
     assert torch.equal(host[n:].view(torch.int16), v.cpu().view(torch.int16).ravel())
+
+
+def test_multi_layer_offload_and_reload_schedule_with_double_buffered_kv():
+    """Algorithm 1 over a stack of layers.  Prefill: layer l's K/V are produced on the main stream into
+    one of TWO device buffers, offloaded on the side stream under that layer's MLP, and the buffer is
+    reused by layer l+2 only after done_event of layer l.  Decode: the caches come back with
+    mom_kv_reload, layer l+1 prefetched while layer l is in use.  Every layer's bytes must survive."""
+    dev = _dev()
+    L = 6
+    wl = synth.Workload("stack", S=8192, H=2048, I=8192, mini_seq=2048, kv_heads=8, seed=12)
+    kvw = synth.Workload("stackkv", S=2048, H=32, I=32, mini_seq=0, kv_heads=8, seed=13)    # 4 MiB per tensor: a copy is shorter than an MLP
+    x, wg, wu, wd = synth.mlp_inputs(wl, device=dev)
+    base_k, base_v = synth.kv_inputs(kvw, device=dev)
+    alone, _ = run_mlp(x, wg, wu, wd, wl.mini_seq)
+    expect = [((base_k * float(l + 1)).cpu(), (base_v * -float(l + 1)).cpu()) for l in range(L)]
+    kbuf = [torch.empty_like(base_k) for _ in range(2)]
+    vbuf = [torch.empty_like(base_v) for _ in range(2)]
+    n = base_k.numel()
+    host = [torch.empty(2 * n, dtype=torch.bfloat16).pin_memory() for _ in range(L)]
+    for h in host:
+        h.zero_()
+    main, side = torch.cuda.current_stream(), torch.cuda.Stream()
+    order = [torch.cuda.Event() for _ in range(L)]
+    done = [torch.cuda.Event() for _ in range(L)]
+    for e in order + done:
+        e.record(main)
+    outs = [torch.empty_like(x) for _ in range(L)]
+    ws = torch.empty(binding.mom_mlp_workspace_bytes(wl.S, wl.H, wl.I, wl.mini_seq), dtype=torch.uint8, device=dev)
+    for l in range(L):                                         # a first copy maps the pinned pages (slow)
+        kbuf[0].zero_(); vbuf[0].zero_()
+        binding.mom_kv_offload(kbuf[0], vbuf[0], host[l], side, producer_stream=main, order_event=order[l],
+                               done_event=done[l])
+    torch.cuda.synchronize()
+    for l in range(L):
+        b = l % 2
+        if l >= 2:
+            main.wait_event(done[l - 2])                       # buffer b is free once layer l-2 is on the host
+        torch.mul(base_k, float(l + 1), out=kbuf[b])           # "attention" of layer l writes its K/V
+        torch.mul(base_v, -float(l + 1), out=vbuf[b])
+        binding.mom_kv_offload(kbuf[b], vbuf[b], host[l], side, producer_stream=main, order_event=order[l],
+                               done_event=done[l])
+        binding.mom_mlp_prefill(x, wg, wu, wd, wl.mini_seq, outs[l], ws, stream=main)
+    torch.cuda.synchronize()
+    for l in range(L):
+        assert bits_equal(outs[l], alone), f"layer {l}: MLP output changed under the offload"
+        assert torch.equal(host[l][:n].view(torch.int16), expect[l][0].view(torch.int16).ravel()), f"K of layer {l}"
+        assert torch.equal(host[l][n:].view(torch.int16), expect[l][1].view(torch.int16).ravel()), f"V of layer {l}"
+
+    # decode: reload layer l+1 on the side stream while layer l is being used on the main stream
+    back = [torch.cuda.Event() for _ in range(L)]
+    used = [torch.cuda.Event() for _ in range(L)]
+    for e in back + used:
+        e.record(main)
+    exp_dev = [(ek.to(dev), ev.to(dev)) for ek, ev in expect]
+    flags = torch.zeros(2 * L, dtype=torch.bool, device=dev)
+    torch.cuda.synchronize()
+    binding.mom_kv_reload(host[0], kbuf[0], vbuf[0], side, done_event=back[0])
+    for l in range(L):
+        b = l % 2
+        if l + 1 < L:
+            if l >= 1:
+                side.wait_event(used[l - 1])                   # the other buffer is free once layer l-1 was used
+            binding.mom_kv_reload(host[l + 1], kbuf[1 - b], vbuf[1 - b], side, done_event=back[l + 1])
+        main.wait_event(back[l])
+        flags[2 * l] = (kbuf[b].view(torch.int16) == exp_dev[l][0].view(torch.int16)).all()
+        flags[2 * l + 1] = (vbuf[b].view(torch.int16) == exp_dev[l][1].view(torch.int16)).all()
+        used[l].record(main)
+    torch.cuda.synchronize()
+    assert bool(flags.all()), f"reloaded layers differ: {flags.cpu().tolist()}"
 
 
 # ------------------------------------------------------------------ full-size workloads, sampled rows
