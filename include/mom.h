@@ -149,7 +149,9 @@ int mom_kv_offload(const void *k, const void *v, void *pinned_host, void *stream
  * KV-cache reload before decode (Algorithm 1, if-branch: "transfer offloaded cache back to GPU";
  * Section 3.2): the mirror of mom_kv_offload.  Asynchronous copy of bytes_each bytes from
  * `pinned_host` (host, page-locked; k at offset 0, v at offset bytes_each) into device k and v
- * on `stream`; `done_event`, if not NULL, is recorded after both copies.
+ * on `stream`; `done_event`, if not NULL, is recorded after both copies.  Ordering is the
+ * caller's: make `stream` wait for the last work that still reads the old contents of k and v
+ * before this call, and make the consumers of k and v wait for `done_event`.
  */
 int mom_kv_reload(const void *pinned_host, void *k, void *v, void *stream, size_t bytes_each,
                   void *done_event);

@@ -115,7 +115,9 @@ def mom_lmhead_last(x_last, W_lm, logits, stream=None, check=True):
 
 
 def mom_kv_offload(k, v, pinned_host, stream, producer_stream=None, order_event=None, done_event=None):
-    """Copy device k, v (same byte size) to the pinned host tensor (k then v) on `stream`."""
+    """Copy device k, v (same byte size) to the pinned host tensor (k then v) on `stream`.
+    With order_event the copy is ordered after the work already enqueued on producer_stream
+    (None = the default stream); done_event is recorded after both copies."""
     nb = _nbytes(k)
     if _nbytes(v) != nb or _nbytes(pinned_host) < 2 * nb:
         raise ValueError("k and v must have equal byte size and pinned_host must hold both")
