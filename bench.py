@@ -176,15 +176,37 @@ def extras(args, binding, synth, torch, wl, tensors, out, dev):
     """Side measurements (not the headline): mini_seq sweep, LM-head GEMV bandwidth, KV offload overlap."""
     S, H, I = wl.S, wl.H, wl.I
     ex = {"sweep": []}
+    side2 = torch.cuda.Stream()
+    pev = [torch.cuda.Event() for _ in range(5)]
+    for e in pev:
+        e.record(torch.cuda.current_stream())
     # 128..512 is the regime of whole-forward chunked prefill (the paper's comparison, Appendix B/C), where the
     # weights are re-read once per 128..512 rows and the path leaves the compute-bound regime
     for C in (128, 256, 512, 1024, 2048, 4096, 8192, 0):
         nb = binding.mom_mlp_workspace_bytes(S, H, I, C)
         ws = torch.empty(nb, dtype=torch.uint8, device=dev)
         sec = time_mlp(binding, torch, tensors, C, out, ws, max(3, args.steps // 2), 2)
-        ex["sweep"].append({"mini_seq": C or S, "workspace_bytes": nb, "ms": round(sec * 1e3, 3),
-                            "tflops": round(6.0 * S * H * I / sec / 1e12, 1)})
+        row = {"mini_seq": C or S, "workspace_bytes": nb, "ms": round(sec * 1e3, 3),
+               "tflops": round(6.0 * S * H * I / sec / 1e12, 1)}
         del ws
+        # the same step through mom_mlp_prefill_pipelined: down(c) on a second stream beside gate/up(c+1),
+        # two workspace halves
+        nb2 = binding.mom_mlp_pipelined_workspace_bytes(S, H, I, C)
+        ws2 = torch.empty(nb2, dtype=torch.uint8, device=dev)
+        x, wg, wu, wd = tensors
+        main = torch.cuda.current_stream()
+        reps = max(3, args.steps // 2)
+        for i in range(2 + reps):
+            if i == 2:
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+            binding.mom_mlp_prefill_pipelined(x, wg, wu, wd, C, out, ws2, main, side2, pev)
+        torch.cuda.synchronize()
+        sec2 = (time.perf_counter() - t0) / reps
+        row["pipelined"] = {"workspace_bytes": nb2, "ms": round(sec2 * 1e3, 3),
+                            "tflops": round(6.0 * S * H * I / sec2 / 1e12, 1)}
+        ex["sweep"].append(row)
+        del ws2
     # LM head GEMV at the Llama-3 vocabulary
     lm = synth.Workload("lm", S=1, H=H, I=I, mini_seq=0, V=128256)
     xl, wlm = synth.lmhead_inputs(lm, device=dev)

@@ -87,6 +87,28 @@ int mom_mlp_prefill(const void *x, const void *W_gate, const void *W_up, const v
                     void *out, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * The same computation and the same bits as mom_mlp_prefill, scheduled on two streams with a
+ * double-buffered workspace (2 * C * I * 2 bytes: still O(C*I), the bound of the paper's Eq. 3):
+ * the down projection of mini-sequence c runs on `stream2` beside the gate/up projection of
+ * mini-sequence c+1 on `stream`, so the CUs that the last, partly filled round of tiles of one
+ * kernel leaves idle work on the other.  Pays off when a mini-sequence has few tiles (mini_seq
+ * of 2048 rows and below on a 256-CU device); with many it equals mom_mlp_prefill.
+ *   workspace        at least mom_mlp_pipelined_workspace_bytes(S,H,I,mini_seq) bytes
+ *   stream, stream2  two streams of the current device (stream2 should differ from stream).  The
+ *                    call orders stream2 after the work already enqueued on stream, and stream
+ *                    after the last kernel on stream2: the caller synchronises `stream` only.
+ *   events           host array of 5 hipEvent_t created by the caller (disable-timing events
+ *                    are fine); they are re-recorded freely during the call
+ * With a single mini-sequence (mini_seq 0 or >= S), or when the down projection of one
+ * mini-sequence fills more than half of the CUs by itself, this is mom_mlp_prefill on `stream`.
+ */
+size_t mom_mlp_pipelined_workspace_bytes(int64_t S, int64_t H, int64_t I, int64_t mini_seq);
+int mom_mlp_prefill_pipelined(const void *x, const void *W_gate, const void *W_up, const void *W_down,
+                              int64_t S, int64_t H, int64_t I, int64_t mini_seq,
+                              void *out, void *workspace, size_t workspace_bytes,
+                              void *stream, void *stream2, void **events);
+
+/*
  * The same computation with a HIP event recorded on `stream` before the first
  * kernel and after every kernel: events[0], then for mini-sequence c the event
  * events[1+2c] after its gate/up kernel and events[2+2c] after its down kernel.

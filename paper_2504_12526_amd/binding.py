@@ -14,6 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmom.so")
 
 SYMBOLS = ("mom_status_string", "mom_mlp_workspace_bytes", "mom_mlp_prefill", "mom_mlp_prefill_events",
+           "mom_mlp_pipelined_workspace_bytes", "mom_mlp_prefill_pipelined",
            "mom_lmhead_last", "mom_mlp_last", "mom_kv_offload", "mom_kv_reload")
 
 MOM_OK, MOM_ERR_NULL, MOM_ERR_SHAPE, MOM_ERR_ALIGN, MOM_ERR_ALIAS, MOM_ERR_WORKSPACE, MOM_ERR_HIP = range(7)
@@ -45,6 +46,11 @@ def lib():
         L.mom_mlp_prefill_events.restype = ctypes.c_int
         L.mom_mlp_prefill_events.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, vp, vp, sz, vp,
                                              ctypes.POINTER(vp), i64]
+        L.mom_mlp_pipelined_workspace_bytes.restype = sz
+        L.mom_mlp_pipelined_workspace_bytes.argtypes = [i64, i64, i64, i64]
+        L.mom_mlp_prefill_pipelined.restype = ctypes.c_int
+        L.mom_mlp_prefill_pipelined.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, vp, vp, sz, vp, vp,
+                                                ctypes.POINTER(vp)]
         L.mom_lmhead_last.restype = ctypes.c_int
         L.mom_lmhead_last.argtypes = [vp, vp, i64, vp, i64, vp]
         L.mom_kv_offload.restype = ctypes.c_int
@@ -102,6 +108,25 @@ def mom_mlp_prefill_events(x, W_gate, W_up, W_down, mini_seq, out, workspace, ev
                                       arr, len(events))
     if rc != MOM_OK:
         raise MomError(rc, "mom_mlp_prefill_events")
+    return rc
+
+
+def mom_mlp_pipelined_workspace_bytes(S, H, I, mini_seq):
+    return int(lib().mom_mlp_pipelined_workspace_bytes(int(S), int(H), int(I), int(mini_seq)))
+
+
+def mom_mlp_prefill_pipelined(x, W_gate, W_up, W_down, mini_seq, out, workspace, stream, stream2, events,
+                              check=True):
+    """As mom_mlp_prefill with down(c) on stream2 beside gate/up(c+1) on stream; workspace of
+    mom_mlp_pipelined_workspace_bytes; events: 4 torch.cuda.Event whose handles exist."""
+    S, H = x.shape
+    I = W_gate.shape[0]
+    arr = None if events is None else (ctypes.c_void_p * len(events))(*[e.cuda_event for e in events])
+    rc = lib().mom_mlp_prefill_pipelined(_ptr(x), _ptr(W_gate), _ptr(W_up), _ptr(W_down), S, H, I, int(mini_seq),
+                                         _ptr(out), _ptr(workspace), _nbytes(workspace), _stream(stream),
+                                         _stream(stream2), arr)
+    if check and rc != MOM_OK:
+        raise MomError(rc, "mom_mlp_prefill_pipelined")
     return rc
 
 

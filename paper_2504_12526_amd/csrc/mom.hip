@@ -59,7 +59,8 @@ int compute_units() {
 
 template <int EPI>
 hipError_t launch_gemm(const unsigned short* X, const unsigned short* W0, const unsigned short* W1,
-                       unsigned short* O, int M, int N, int K, hipStream_t st) {
+                       unsigned short* O, int M, int N, int K, hipStream_t st, bool* used_small = nullptr,
+                       bool never_small = false) {
     momk::GemmArgs a;
     a.X = X; a.W0 = W0; a.W1 = W1; a.O = O;
     a.M = M; a.N = N; a.K = K;
@@ -84,7 +85,9 @@ hipError_t launch_gemm(const unsigned short* X, const unsigned short* W0, const 
         // MOM_GEMM_TILE=128|256 in the environment overrides the choice (for tests, which need both
         // forms on shapes of every size).
         const char* force = getenv("MOM_GEMM_TILE");
-        const bool small = force && force[0] ? (strcmp(force, "128") == 0) : (tiles * 4 <= (int64_t)cus * 3);
+        const bool small = force && force[0] ? (strcmp(force, "128") == 0)
+                                             : (!never_small && tiles * 4 <= (int64_t)cus * 3);
+        if (used_small) *used_small = small;
         if (small) {
             if (set_tiles(128) > (int64_t)0x1fffffff) return hipErrorInvalidValue;
             hipLaunchKernelGGL((momk::gemm4_kernel<EPI, 128>), dim3((unsigned)(a.tiles_per_xcd * 8)),
@@ -145,6 +148,59 @@ int mlp_driver(const void* x, const void* wg, const void* wu, const void* wd, in
     return MOM_OK;
 }
 
+// The same loop on two streams with two workspace halves: the down projection of mini-sequence c
+// (stream B) runs beside the gate/up projection of mini-sequence c+1 (stream A), so that the CUs
+// one kernel's last, partly filled round of tiles leaves idle take tiles of the other.
+//   A: [wait D(c-2)]  gate/up(c) -> half c%2   record G(c)
+//   B:  wait G(c)     down(c)   <- half c%2    record D(c)
+// ev[0..1] = G of even/odd c, ev[2..3] = D of even/odd c.
+int mlp_pipelined(const void* x, const void* wg, const void* wu, const void* wd, int64_t S, int64_t H, int64_t I,
+                  int64_t mini_seq, void* out, void* ws, size_t ws_bytes, hipStream_t sa, hipStream_t sb,
+                  hipEvent_t* ev) {
+    const int64_t C = effective_chunk(S, mini_seq);
+    const int64_t n = (S + C - 1) / C;
+    const unsigned short* xs = static_cast<const unsigned short*>(x);
+    unsigned short* os = static_cast<unsigned short*>(out);
+    unsigned short* half[2] = {static_cast<unsigned short*>(ws), static_cast<unsigned short*>(ws) + (size_t)C * I};
+    (void)ws_bytes;
+    // B starts after everything already enqueued on A (the inputs)
+    if (hipEventRecord(ev[2], sa) != hipSuccess || hipStreamWaitEvent(sb, ev[2], 0) != hipSuccess) return MOM_ERR_HIP;
+    // Full-size tiles for a down projection that runs beside a gate/up kernel pay as long as its
+    // one round of long tiles (K = I) does not outlast the gate/up kernel on the remaining CUs by much.
+    const int cus = compute_units();
+    const int64_t tm = (C + momk::kBM - 1) / momk::kBM;
+    const int64_t tiles_dn = tm * ((H + momk::kBW - 1) / momk::kBW), tiles_gu = tm * ((I + momk::kBW / 2 - 1) / (momk::kBW / 2));
+    const int64_t cus_left = cus - tiles_dn > 0 ? cus - tiles_dn : 1;
+    const bool down_big_pays = 2 * I <= 3 * ((tiles_gu + cus_left - 1) / cus_left) * H;
+    bool gateup_small = false;
+    for (int64_t c = 0; c < n; ++c) {
+        const int64_t r0 = c * C;
+        const int rows = (int)((r0 + C <= S) ? C : (S - r0));
+        const int h = (int)(c & 1);
+        if (c >= 2 && hipStreamWaitEvent(sa, ev[2 + h], 0) != hipSuccess) return MOM_ERR_HIP;
+        // gate/up(c) is held until down(c-1) has been handed to the device: its few, long tiles must
+        // get their CUs before the many tiles of this kernel take the whole chip for a round
+        if (c >= 1 && hipStreamWaitEvent(sa, ev[4], 0) != hipSuccess) return MOM_ERR_HIP;
+        if (launch_gemm<momk::EPI_GATEUP>(xs + r0 * H, static_cast<const unsigned short*>(wg),
+                                          static_cast<const unsigned short*>(wu), half[h], rows, (int)I, (int)H, sa,
+                                          &gateup_small) != hipSuccess)
+            return MOM_ERR_HIP;
+        if (hipEventRecord(ev[h], sa) != hipSuccess || hipStreamWaitEvent(sb, ev[h], 0) != hipSuccess)
+            return MOM_ERR_HIP;
+        if (hipEventRecord(ev[4], sb) != hipSuccess) return MOM_ERR_HIP;
+        // beside a gate/up kernel that fills the chip, full-size tiles are the efficient form for the
+        // down projection however few they are; the last one runs alone and follows the usual rule
+        const bool beside_big = (c + 1 < n) && !gateup_small && down_big_pays;
+        if (launch_gemm<momk::EPI_DOWN>(half[h], static_cast<const unsigned short*>(wd), nullptr, os + r0 * H, rows,
+                                        (int)H, (int)I, sb, nullptr, beside_big) != hipSuccess)
+            return MOM_ERR_HIP;
+        if (hipEventRecord(ev[2 + h], sb) != hipSuccess) return MOM_ERR_HIP;
+    }
+    // A continues after the last down projection: the caller synchronises A only
+    if (hipStreamWaitEvent(sa, ev[2 + (int)((n - 1) & 1)], 0) != hipSuccess) return MOM_ERR_HIP;
+    return MOM_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -172,6 +228,48 @@ int mom_mlp_prefill(const void* x, const void* W_gate, const void* W_up, const v
                     size_t workspace_bytes, void* stream) {
     return mlp_driver(x, W_gate, W_up, W_down, S, H, I, mini_seq, out, workspace, workspace_bytes, stream,
                       nullptr, 0);
+}
+
+size_t mom_mlp_pipelined_workspace_bytes(int64_t S, int64_t H, int64_t I, int64_t mini_seq) {
+    const size_t one = mom_mlp_workspace_bytes(S, H, I, mini_seq);
+    if (one == 0) return 0;
+    const int64_t C = effective_chunk(S, mini_seq);
+    return (S + C - 1) / C > 1 ? 2 * one : one;
+}
+
+int mom_mlp_prefill_pipelined(const void* x, const void* W_gate, const void* W_up, const void* W_down, int64_t S,
+                              int64_t H, int64_t I, int64_t mini_seq, void* out, void* workspace,
+                              size_t workspace_bytes, void* stream, void* stream2, void** events) {
+    int rc = validate_mlp(x, W_gate, W_up, W_down, S, H, I, mini_seq, out, workspace, workspace_bytes);
+    if (rc != MOM_OK || S == 0) return rc;
+    const size_t need = mom_mlp_pipelined_workspace_bytes(S, H, I, mini_seq);
+    if (workspace_bytes < need) return MOM_ERR_WORKSPACE;
+    const void* ins[4] = {x, W_gate, W_up, W_down};
+    const size_t xb = (size_t)S * H * 2, wb = (size_t)H * I * 2;
+    const size_t inb[4] = {xb, wb, wb, wb};
+    for (int i = 0; i < 4; ++i)
+        if (overlaps(workspace, need, ins[i], inb[i])) return MOM_ERR_ALIAS;
+    if (overlaps(out, xb, workspace, need)) return MOM_ERR_ALIAS;
+    const int64_t C = effective_chunk(S, mini_seq);
+    if ((S + C - 1) / C == 1)      // a single mini-sequence: nothing to overlap
+        return mlp_driver(x, W_gate, W_up, W_down, S, H, I, mini_seq, out, workspace, workspace_bytes, stream,
+                          nullptr, 0);
+    if (!events) return MOM_ERR_NULL;
+    hipEvent_t ev[5];
+    for (int i = 0; i < 5; ++i) {
+        if (!events[i]) return MOM_ERR_NULL;
+        ev[i] = static_cast<hipEvent_t>(events[i]);
+    }
+    // nothing to gain: a down projection that fills more than half of the CUs by itself was measured
+    // to run no faster beside the next gate/up kernel
+    const int cus = compute_units();
+    if (cus <= 0) return MOM_ERR_HIP;
+    const int64_t tiles_dn = ((C + momk::kBM - 1) / momk::kBM) * ((H + momk::kBW - 1) / momk::kBW);
+    if (2 * tiles_dn > cus)
+        return mlp_driver(x, W_gate, W_up, W_down, S, H, I, mini_seq, out, workspace, workspace_bytes, stream,
+                          nullptr, 0);
+    return mlp_pipelined(x, W_gate, W_up, W_down, S, H, I, mini_seq, out, workspace, workspace_bytes,
+                         static_cast<hipStream_t>(stream), static_cast<hipStream_t>(stream2), ev);
 }
 
 int mom_mlp_prefill_events(const void* x, const void* W_gate, const void* W_up, const void* W_down,

@@ -67,6 +67,30 @@ def test_mlp_argument_validation_happens_before_any_launch():
     assert _call(S=0, x=0, out=0, ws=0) == binding.MOM_OK                   # empty input: no-op
 
 
+def test_pipelined_workspace_and_argument_validation():
+    pb, wb = binding.mom_mlp_pipelined_workspace_bytes, binding.mom_mlp_workspace_bytes
+    for wl in synth.WORKLOADS.values():
+        assert pb(wl.S, wl.H, wl.I, wl.mini_seq) == 2 * wb(wl.S, wl.H, wl.I, wl.mini_seq)   # two halves, still O(C*I)
+        assert pb(wl.S, wl.H, wl.I, 0) == wb(wl.S, wl.H, wl.I, 0)                           # one mini-sequence: one half
+    assert pb(0, 64, 96, 8) == 0 and pb(10, 64, 96, -1) == 0
+    vp = ctypes.c_void_p
+
+    def call(x=0x1000, wg=0x2000000, wu=0x3000000, wd=0x4000000, S=64, H=64, I=96, C=16, out=0x5000000,
+             ws=0x6000000, wsb=None, events=True):
+        if wsb is None:
+            wsb = pb(S, H, I, C)
+        ev = (vp * 5)(*[vp(0x10 + i) for i in range(5)]) if events else None
+        return binding.lib().mom_mlp_prefill_pipelined(vp(x), vp(wg), vp(wu), vp(wd), S, H, I, C, vp(out), vp(ws),
+                                                       wsb, None, None, ev)
+    assert call(H=48) == binding.MOM_ERR_SHAPE
+    assert call(wu=0) == binding.MOM_ERR_NULL
+    assert call(out=0x5000004) == binding.MOM_ERR_ALIGN
+    assert call(wsb=wb(64, 64, 96, 16)) == binding.MOM_ERR_WORKSPACE          # one half is not enough
+    assert call(ws=0x5000000 - 16 * 96 * 2 - 32) == binding.MOM_ERR_ALIAS    # second half runs into out
+    assert call(events=False) == binding.MOM_ERR_NULL                         # several mini-sequences need events
+    assert call(S=0, x=0, out=0, ws=0) == binding.MOM_OK
+
+
 def test_lmhead_and_offload_argument_validation():
     vp = ctypes.c_void_p
     L = binding.lib()

@@ -53,6 +53,22 @@ def run_mlp(x, wg, wu, wd, mini_seq, stream=None):
     return out, nbytes
 
 
+def run_mlp_pipelined(x, wg, wu, wd, mini_seq):
+    """mom_mlp_prefill_pipelined on the current stream plus a side stream."""
+    S, H = x.shape
+    I = wg.shape[0]
+    out = torch.empty((S, H), dtype=torch.bfloat16, device=x.device)
+    nbytes = binding.mom_mlp_pipelined_workspace_bytes(S, H, I, mini_seq)
+    ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=x.device)
+    main, side = torch.cuda.current_stream(), torch.cuda.Stream()
+    events = [torch.cuda.Event() for _ in range(5)]
+    for e in events:
+        e.record(main)
+    binding.mom_mlp_prefill_pipelined(x, wg, wu, wd, mini_seq, out, ws, main, side, events)
+    main.synchronize()                      # the contract: synchronising `stream` is enough
+    return out, nbytes
+
+
 def bits_equal(a, b):
     return torch.equal(a.view(torch.int16), b.view(torch.int16))
 
@@ -90,6 +106,33 @@ def test_ragged_shapes_match_oracle(S, H, I):
         out, nbytes = run_mlp(xd, wgd, wud, wdd, C)
         assert nbytes == min(C, S) * I * 2
         assert bits_equal(out, full), f"C={C}"
+
+
+@pytest.mark.parametrize("S,H,I", [(300, 96, 160), (257, 64, 64), (700, 384, 640), (1100, 256, 1024), (2500, 512, 512)])
+def test_pipelined_schedule_gives_the_same_bits(S, H, I):
+    """Two streams and a double-buffered workspace change the schedule, not one bit of the result."""
+    dev = _dev()
+    wl = synth.Workload("pipe", S=S, H=H, I=I, mini_seq=0, seed=S + 2 * I, w_std=0.05)
+    xd, wgd, wud, wdd = (t.to(dev) for t in synth.mlp_inputs(wl))
+    full, _ = run_mlp(xd, wgd, wud, wdd, 0)
+    for C in (7, 100, 256, 300, S, 0):
+        out, nbytes = run_mlp_pipelined(xd, wgd, wud, wdd, C)
+        n = 1 if (C == 0 or C >= S) else -(-S // C)
+        assert nbytes == (2 if n > 1 else 1) * min(C if C else S, S) * I * 2
+        assert bits_equal(out, full), f"C={C}"
+    # back to back on the same streams and workspace, without a synchronisation in between
+    ws = torch.empty(binding.mom_mlp_pipelined_workspace_bytes(S, H, I, 128), dtype=torch.uint8, device=dev)
+    main, side = torch.cuda.current_stream(), torch.cuda.Stream()
+    events = [torch.cuda.Event() for _ in range(5)]
+    for e in events:
+        e.record(main)
+    outs = [torch.empty_like(xd) for _ in range(3)]
+    for o in outs:
+        binding.mom_mlp_prefill_pipelined(xd, wgd, wud, wdd, 128, o, ws, main, side, events)
+    main.synchronize()
+    for o in outs:
+        assert bits_equal(o, full)
+    torch.cuda.synchronize()
 
 
 def test_row_permutation_and_independence_on_gpu():
@@ -422,6 +465,12 @@ def test_llama3_8b_32k_full_size():
     b, _ = run_mlp(x, wg, wu, wd, 0)
     assert bits_equal(a, b)
     assert bits_equal(a, out[: wl.S - 77].contiguous())     # same seed, same leading rows
+    # the two-stream schedule at mini-sequence sizes where it overlaps the two projections
+    x, wg, wu, wd = synth.mlp_inputs(wl, device=dev)
+    for C in (512, 1024, 2048, 4096):
+        p, nb = run_mlp_pipelined(x, wg, wu, wd, C)
+        assert nb == 2 * C * wl.I * 2
+        assert bits_equal(p, out), f"pipelined C={C}"
 
 
 def test_llama3_8b_128k_full_size_with_offload_and_lmhead():
