@@ -123,3 +123,11 @@ def test_product_does_not_import_the_oracle():
             if f.endswith((".py", ".hip", ".inc", ".h")):
                 text = open(os.path.join(dirpath, f)).read()
                 assert not re.search(r"import\s+oracle|from\s+oracle|oracle\.|oracle/|mom_oracle", text), f
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0
+    assert "one GPU" in (r.stderr + r.stdout)
