@@ -132,6 +132,11 @@ def test_pipelined_schedule_gives_the_same_bits(S, H, I):
     main.synchronize()
     for o in outs:
         assert bits_equal(o, full)
+    # degenerate but legal: both streams the same
+    o1 = torch.empty_like(xd)
+    binding.mom_mlp_prefill_pipelined(xd, wgd, wud, wdd, 128, o1, ws, main, main, events)
+    main.synchronize()
+    assert bits_equal(o1, full)
     torch.cuda.synchronize()
 
 
