@@ -41,7 +41,7 @@ class Workload:
     w_std: float = 0.02
 
 
-# BASELINE.json "configs", in order.
+# The benchmark configurations, in order: a tiny correctness case, then layer shapes of the model families the paper evaluates.
 WORKLOADS = {
     "tiny": Workload("tiny", S=512, H=256, I=1024, mini_seq=128, V=4096),
     "llama3_8b_32k": Workload("llama3_8b_32k", S=32768, H=4096, I=14336, mini_seq=4096,
