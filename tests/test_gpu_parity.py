@@ -214,7 +214,8 @@ def test_library_allocates_nothing():
 
 # ------------------------------------------------------------------ LM head and last-token branch
 
-@pytest.mark.parametrize("V,H", [(4096, 256), (1001, 4096), (3, 32), (16, 3584), (5000, 416)])
+@pytest.mark.parametrize("V,H", [(4096, 256), (1001, 4096), (3, 32), (16, 3584), (5000, 416),
+                                 (33, 32768)])            # the longest supported row
 def test_lmhead_matches_oracle(V, H):
     dev = _dev()
     wl = synth.Workload("lm", S=1, H=H, I=32, mini_seq=0, V=V, seed=V % 97)
@@ -250,7 +251,8 @@ def test_last_token_branch_matches_oracle():
     assert np.abs(logits.cpu().numpy() - l_own).max() <= 1e-5 * np.abs(l_own).max()
 
 
-@pytest.mark.parametrize("H,I", [(256, 1024), (4096, 14336), (3584, 18944), (96, 160), (32, 32)])
+@pytest.mark.parametrize("H,I", [(256, 1024), (4096, 14336), (3584, 18944), (96, 160), (32, 32),
+                                 (32768, 64), (64, 32768)])      # the largest supported H and I
 def test_last_token_mlp_gemv_matches_oracle(H, I):
     """mom_mlp_last (one-token matrix-vector path) against the oracle and against the matrix-core path."""
     dev = _dev()
@@ -540,3 +542,29 @@ def test_gemm_tile_forms_give_identical_bits(S, H, I, monkeypatch):
     for i, o in enumerate(outs[1:]):
         assert bits_equal(outs[0], o), f"form {i + 1}"
     assert_close_to_oracle(_f32(outs[0]), ref, f"tile forms S={S} H={H} I={I}")
+
+
+def test_bench_prints_the_contract_json_line():
+    """bench.py on the small workload: one JSON line with the keys the harness reads."""
+    import json
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--workload", "tiny", "--steps", "3",
+                        "--warmup", "1", "--cpu-seconds", "0.5"], capture_output=True, text=True, timeout=170)
+    assert r.returncode == 0, r.stderr[-2000:]
+    lines = [l for l in r.stdout.splitlines() if l.startswith("{")]
+    assert len(lines) == 1
+    d = json.loads(lines[0])
+    for k in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling",
+              "vs_baseline", "dtype", "data", "config", "roofline", "cpu_baseline"):
+        assert k in d, k
+    assert d["n_gpus"] == 1 and d["steps"] == 3 and d["unit"] == "TFLOP/s" and d["dtype"] == "bf16"
+    assert "workload" in d["config"] and d["vs_baseline"] is None
+    for k in ("bound", "achieved", "peak", "unit", "frac", "traffic"):
+        assert k in d["roofline"], k
+    assert abs(d["roofline"]["frac"] - d["roofline"]["achieved"] / d["roofline"]["peak"]) < 1e-3
+    for k in ("value", "unit", "cores", "kind", "sample"):
+        assert k in d["cpu_baseline"], k
+    assert d["cpu_baseline"]["kind"] == "oracle"
