@@ -80,7 +80,7 @@ size_t mom_mlp_workspace_bytes(int64_t S, int64_t H, int64_t I, int64_t mini_seq
  * S = 0 is a no-op returning MOM_OK.  H and I must be positive multiples of 32.
  * All work is enqueued on `stream` in order (2 kernels per mini-sequence).
  * The kernels exist in several tile forms with bit-identical results; the library picks one per
- * launch.  Testing aid: MOM_GEMM_TILE=128 or 256 in the environment forces the form.
+ * launch.  Testing aid: MOM_GEMM_TILE = 256, 128, 128deep or 128shallow in the environment forces the form.
  */
 int mom_mlp_prefill(const void *x, const void *W_gate, const void *W_up, const void *W_down,
                     int64_t S, int64_t H, int64_t I, int64_t mini_seq,

@@ -82,16 +82,24 @@ hipError_t launch_gemm(const unsigned short* X, const unsigned short* W0, const 
     if (K % 64 == 0) {
         const int cus = compute_units();
         if (cus <= 0) return hipErrorInvalidDevice;
-        // MOM_GEMM_TILE=128|256 in the environment overrides the choice (for tests, which need both
-        // forms on shapes of every size).
+        // MOM_GEMM_TILE = 256 | 128 | 128deep | 128shallow in the environment overrides the choice (for
+        // tests, which need every form on shapes of every size).
         const char* force = getenv("MOM_GEMM_TILE");
-        const bool small = force && force[0] ? (strcmp(force, "128") == 0)
-                                             : (!never_small && tiles * 4 <= (int64_t)cus * 3);
+        const bool forced = force && force[0];
+        const bool small = forced ? (strncmp(force, "128", 3) == 0)
+                                  : (!never_small && tiles * 4 <= (int64_t)cus * 3);
         if (used_small) *used_small = small;
         if (small) {
-            if (set_tiles(128) > (int64_t)0x1fffffff) return hipErrorInvalidValue;
-            hipLaunchKernelGGL((momk::gemm4_kernel<EPI, 128>), dim3((unsigned)(a.tiles_per_xcd * 8)),
-                               dim3(momk::k4Threads), 0, st, a);
+            const int64_t tiles128 = set_tiles(128);
+            if (tiles128 > (int64_t)0x1fffffff) return hipErrorInvalidValue;
+            // at most one workgroup per CU anyway: give it the whole LDS as a ring of five stages
+            const bool deep = forced && force[3] ? (strcmp(force, "128deep") == 0) : (tiles128 <= cus);
+            if (deep)
+                hipLaunchKernelGGL((momk::gemm4_kernel<EPI, 128, true>), dim3((unsigned)(a.tiles_per_xcd * 8)),
+                                   dim3(momk::k4Threads), 0, st, a);
+            else
+                hipLaunchKernelGGL((momk::gemm4_kernel<EPI, 128, false>), dim3((unsigned)(a.tiles_per_xcd * 8)),
+                                   dim3(momk::k4Threads), 0, st, a);
         } else {
             hipLaunchKernelGGL((momk::gemm4_kernel<EPI, 256>), dim3((unsigned)(a.tiles_per_xcd * 8)),
                                dim3(momk::k4Threads), 0, st, a);

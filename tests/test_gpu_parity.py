@@ -524,16 +524,17 @@ def test_mistral_7b_448k_full_size():
 
 @pytest.mark.parametrize("S,H,I", [(257, 64, 64), (300, 128, 192), (700, 384, 640), (1100, 256, 1024)])
 def test_gemm_tile_forms_give_identical_bits(S, H, I, monkeypatch):
-    """The 256-tile and the 128-tile form of the four-wavefront kernel (the library picks one by the
-    number of tiles in a launch; MOM_GEMM_TILE overrides it) agree bit for bit, with each other
-    and across mini_seq, and match the oracle."""
+    """The 256-tile form and the two 128-tile forms (shallow and deep LDS ring) of the four-wavefront
+    kernel - the library picks one by the number of tiles in a launch; MOM_GEMM_TILE overrides it -
+    agree bit for bit, with each other and across mini_seq, and match the oracle."""
     dev = _dev()
     wl = synth.Workload("tiles", S=S, H=H, I=I, mini_seq=0, seed=S + I, w_std=0.05)
     x, wg, wu, wd = synth.mlp_inputs(wl)
     ref = oracle.mlp_rows(*(synth.bits(t) for t in (x, wg, wu, wd)))
     xd, wgd, wud, wdd = (t.to(dev) for t in (x, wg, wu, wd))
     outs = []
-    for tile, C in (("256", 0), ("128", 0), ("256", 256), ("128", 200), ("", 0)):
+    for tile, C in (("256", 0), ("128deep", 0), ("128shallow", 0), ("256", 256), ("128shallow", 200),
+                    ("128deep", 100), ("128", 0), ("", 0)):
         if tile:
             monkeypatch.setenv("MOM_GEMM_TILE", tile)
         else:
