@@ -38,6 +38,15 @@ def parse():
     return p.parse_args()
 
 
+def device_info(torch, dev):
+    """What the box reports, beside the published peak the roofline divides by: 256 CUs x 4 SIMDs x 1024 bf16
+    flop per clock at the 2.4 GHz peak engine clock = 2.5 PFLOP/s."""
+    p = torch.cuda.get_device_properties(dev)
+    cus = int(p.multi_processor_count)
+    return {"name": p.name, "arch": getattr(p, "gcnArchName", ""), "compute_units": cus,
+            "bf16_mfma_peak_at_2400_mhz_tflops": round(cus * 4 * 1024 * 2.4e9 / 1e12, 1)}
+
+
 def time_mlp(binding, torch, tensors, C, out, ws, steps, warmup):
     x, wg, wu, wd = tensors
     st = torch.cuda.current_stream()
@@ -144,6 +153,7 @@ def main():
                    "S": S, "H": H, "I": I, "mini_seq": C, "mini_sequences": -(-S // C)},
         "pct_bf16_mfma_peak": round(100.0 * tflops / BF16_MFMA_PEAK_TFLOPS, 2),
         "workspace_bytes": ws_bytes, "unchunked_workspace_bytes": S * I * 2,
+        "device": device_info(torch, dev),
         "roofline": {"bound": "mfma", "kernel": ("gemm4_kernel<EPI_GATEUP>" if H % 64 == 0 else "gemm_kernel<EPI_GATEUP>") + " (gate/up GEMM + SiLU*up epilogue)",
                      "achieved": round(gu_tflops, 2), "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(gu_tflops / BF16_MFMA_PEAK_TFLOPS, 4),
