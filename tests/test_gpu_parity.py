@@ -545,6 +545,51 @@ def test_gemm_tile_forms_give_identical_bits(S, H, I, monkeypatch):
     assert_close_to_oracle(_f32(outs[0]), ref, f"tile forms S={S} H={H} I={I}")
 
 
+def test_entry_points_can_be_captured_in_a_hip_graph():
+    """The MLP, LM-head and last-token calls only enqueue kernels (no allocation, no synchronisation),
+    so they can be captured and replayed; every replay, with eager work in between, must give the
+    bits of an eager call on the same buffers."""
+    dev = _dev()
+    wl = synth.Workload("graph", S=1500, H=256, I=1024, mini_seq=512, V=1000, seed=21, w_std=0.05)
+    x, wg, wu, wd = (t.to(dev) for t in synth.mlp_inputs(wl))
+    xl, wlm = (t.to(dev) for t in synth.lmhead_inputs(wl))
+    out = torch.empty_like(x)
+    logits = torch.empty((wl.V,), dtype=torch.float32, device=dev)
+    last = torch.empty((wl.H,), dtype=torch.bfloat16, device=dev)
+    ws = torch.empty(binding.mom_mlp_workspace_bytes(wl.S, wl.H, wl.I, wl.mini_seq), dtype=torch.uint8, device=dev)
+    ws1 = torch.empty(wl.I * 2, dtype=torch.uint8, device=dev)
+
+    def enqueue():
+        binding.mom_mlp_prefill(x, wg, wu, wd, wl.mini_seq, out, ws)
+        binding.mom_mlp_last(x[-1], wg, wu, wd, last, ws1)
+        binding.mom_lmhead_last(xl, wlm, logits)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        enqueue()                                  # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        enqueue()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        x.mul_(-0.5 if rep else 1.0)               # new inputs in the same buffers
+        xl.mul_(2.0)
+        out.zero_(); logits.zero_(); last.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = (out.clone(), logits.clone(), last.clone())
+        out.zero_(); logits.zero_(); last.zero_()
+        enqueue()                                  # eager, same buffers
+        torch.cuda.synchronize()
+        assert bits_equal(got[0], out), f"replay {rep}: MLP"
+        assert torch.equal(got[1], logits), f"replay {rep}: LM head"
+        assert bits_equal(got[2], last), f"replay {rep}: last-token MLP"
+
+
 def test_bench_prints_the_contract_json_line():
     """bench.py on the small workload: one JSON line with the keys the harness reads."""
     import json
