@@ -80,7 +80,8 @@ size_t mom_mlp_workspace_bytes(int64_t S, int64_t H, int64_t I, int64_t mini_seq
  * S = 0 is a no-op returning MOM_OK.  H and I must be positive multiples of 32.
  * All work is enqueued on `stream` in order (2 kernels per mini-sequence).
  * The kernels exist in several tile forms with bit-identical results; the library picks one per
- * launch.  Testing aid: MOM_GEMM_TILE = 256, 128, 128deep or 128shallow in the environment forces the form.
+ * launch.  Testing aid: MOM_GEMM_TILE = <edge> or <edge>x<ring slots> in the environment forces the
+ * form (256, 128, 128x5, 128x10, 64, 64x5, 64x10, 64x20).
  */
 int mom_mlp_prefill(const void *x, const void *W_gate, const void *W_up, const void *W_down,
                     int64_t S, int64_t H, int64_t I, int64_t mini_seq,
@@ -99,8 +100,10 @@ int mom_mlp_prefill(const void *x, const void *W_gate, const void *W_up, const v
  *                    after the last kernel on stream2: the caller synchronises `stream` only.
  *   events           host array of 5 hipEvent_t created by the caller (disable-timing events
  *                    are fine); they are re-recorded freely during the call
- * With a single mini-sequence (mini_seq 0 or >= S), or when the down projection of one
- * mini-sequence fills more than half of the CUs by itself, this is mom_mlp_prefill on `stream`.
+ * With a single mini-sequence (mini_seq 0 or >= S), or where the schedule was measured not to pay
+ * (a down projection that fills more than half of the CUs by itself, or mini-sequences so short
+ * that both projections are latency-bound), this is mom_mlp_prefill on `stream`.  Testing aid:
+ * MOM_PIPELINE=1 in the environment forces the two-stream schedule.
  */
 size_t mom_mlp_pipelined_workspace_bytes(int64_t S, int64_t H, int64_t I, int64_t mini_seq);
 int mom_mlp_prefill_pipelined(const void *x, const void *W_gate, const void *W_up, const void *W_down,

@@ -59,8 +59,7 @@ int compute_units() {
 
 template <int EPI>
 hipError_t launch_gemm(const unsigned short* X, const unsigned short* W0, const unsigned short* W1,
-                       unsigned short* O, int M, int N, int K, hipStream_t st, bool* used_small = nullptr,
-                       bool never_small = false) {
+                       unsigned short* O, int M, int N, int K, hipStream_t st, bool never_small = false) {
     momk::GemmArgs a;
     a.X = X; a.W0 = W0; a.W1 = W1; a.O = O;
     a.M = M; a.N = N; a.K = K;
@@ -82,28 +81,35 @@ hipError_t launch_gemm(const unsigned short* X, const unsigned short* W0, const 
     if (K % 64 == 0) {
         const int cus = compute_units();
         if (cus <= 0) return hipErrorInvalidDevice;
-        // MOM_GEMM_TILE = 256 | 128 | 128deep | 128shallow in the environment overrides the choice (for
-        // tests, which need every form on shapes of every size).
+        // Tile edge and ring depth.  256-tiles unless they would leave a quarter or more of the CUs
+        // without work; then 128-tiles, or 64-tiles when even those fill less than half of the CUs; the
+        // small tiles get a deeper ring the fewer workgroups a CU has to hide latency with.
+        // MOM_GEMM_TILE = <edge> or <edge>x<slots> (256, 128, 128x5, 128x10, 64, 64x5, 64x10, 64x20) in the
+        // environment overrides the choice (for tests, which need every form on shapes of every size).
+        int edge = 256, slots = 0;
         const char* force = getenv("MOM_GEMM_TILE");
-        const bool forced = force && force[0];
-        const bool small = forced ? (strncmp(force, "128", 3) == 0)
-                                  : (!never_small && tiles * 4 <= (int64_t)cus * 3);
-        if (used_small) *used_small = small;
-        if (small) {
-            const int64_t tiles128 = set_tiles(128);
-            if (tiles128 > (int64_t)0x1fffffff) return hipErrorInvalidValue;
-            // at most one workgroup per CU anyway: give it the whole LDS as a ring of five stages
-            const bool deep = forced && force[3] ? (strcmp(force, "128deep") == 0) : (tiles128 <= cus);
-            if (deep)
-                hipLaunchKernelGGL((momk::gemm4_kernel<EPI, 128, true>), dim3((unsigned)(a.tiles_per_xcd * 8)),
-                                   dim3(momk::k4Threads), 0, st, a);
-            else
-                hipLaunchKernelGGL((momk::gemm4_kernel<EPI, 128, false>), dim3((unsigned)(a.tiles_per_xcd * 8)),
-                                   dim3(momk::k4Threads), 0, st, a);
-        } else {
-            hipLaunchKernelGGL((momk::gemm4_kernel<EPI, 256>), dim3((unsigned)(a.tiles_per_xcd * 8)),
-                               dim3(momk::k4Threads), 0, st, a);
+        if (force && force[0]) {
+            edge = atoi(force);
+            const char* x = strchr(force, 'x');
+            slots = x ? atoi(x + 1) : 0;
+            if (edge != 256 && edge != 128 && edge != 64) return hipErrorInvalidValue;
+        } else if (!never_small && tiles * 4 <= (int64_t)cus * 3) {
+            edge = (set_tiles(128) * 2 <= cus) ? 64 : 128;
         }
+        const int64_t t = set_tiles(edge);
+        if (t > (int64_t)0x1fffffff) return hipErrorInvalidValue;
+        if (edge == 256) slots = 5;
+        else if (slots == 0) slots = (edge == 128) ? (t <= cus ? 10 : 5) : (t <= cus ? 20 : (t <= 2 * (int64_t)cus ? 10 : 5));
+        const dim3 grid((unsigned)(a.tiles_per_xcd * 8)), block(momk::k4Threads);
+#define MOM_LAUNCH4(E, S) hipLaunchKernelGGL((momk::gemm4_kernel<EPI, E, S>), grid, block, 0, st, a)
+        if (edge == 256 && slots == 5) MOM_LAUNCH4(256, 5);
+        else if (edge == 128 && slots == 5) MOM_LAUNCH4(128, 5);
+        else if (edge == 128 && slots == 10) MOM_LAUNCH4(128, 10);
+        else if (edge == 64 && slots == 5) MOM_LAUNCH4(64, 5);
+        else if (edge == 64 && slots == 10) MOM_LAUNCH4(64, 10);
+        else if (edge == 64 && slots == 20) MOM_LAUNCH4(64, 20);
+        else return hipErrorInvalidValue;
+#undef MOM_LAUNCH4
         return hipGetLastError();
     }
 #endif
@@ -173,14 +179,6 @@ int mlp_pipelined(const void* x, const void* wg, const void* wu, const void* wd,
     (void)ws_bytes;
     // B starts after everything already enqueued on A (the inputs)
     if (hipEventRecord(ev[2], sa) != hipSuccess || hipStreamWaitEvent(sb, ev[2], 0) != hipSuccess) return MOM_ERR_HIP;
-    // Full-size tiles for a down projection that runs beside a gate/up kernel pay as long as its
-    // one round of long tiles (K = I) does not outlast the gate/up kernel on the remaining CUs by much.
-    const int cus = compute_units();
-    const int64_t tm = (C + momk::kBM - 1) / momk::kBM;
-    const int64_t tiles_dn = tm * ((H + momk::kBW - 1) / momk::kBW), tiles_gu = tm * ((I + momk::kBW / 2 - 1) / (momk::kBW / 2));
-    const int64_t cus_left = cus - tiles_dn > 0 ? cus - tiles_dn : 1;
-    const bool down_big_pays = 2 * I <= 3 * ((tiles_gu + cus_left - 1) / cus_left) * H;
-    bool gateup_small = false;
     for (int64_t c = 0; c < n; ++c) {
         const int64_t r0 = c * C;
         const int rows = (int)((r0 + C <= S) ? C : (S - r0));
@@ -190,17 +188,17 @@ int mlp_pipelined(const void* x, const void* wg, const void* wu, const void* wd,
         // get their CUs before the many tiles of this kernel take the whole chip for a round
         if (c >= 1 && hipStreamWaitEvent(sa, ev[4], 0) != hipSuccess) return MOM_ERR_HIP;
         if (launch_gemm<momk::EPI_GATEUP>(xs + r0 * H, static_cast<const unsigned short*>(wg),
-                                          static_cast<const unsigned short*>(wu), half[h], rows, (int)I, (int)H, sa,
-                                          &gateup_small) != hipSuccess)
+                                          static_cast<const unsigned short*>(wu), half[h], rows, (int)I, (int)H,
+                                          sa) != hipSuccess)
             return MOM_ERR_HIP;
         if (hipEventRecord(ev[h], sa) != hipSuccess || hipStreamWaitEvent(sb, ev[h], 0) != hipSuccess)
             return MOM_ERR_HIP;
         if (hipEventRecord(ev[4], sb) != hipSuccess) return MOM_ERR_HIP;
         // beside a gate/up kernel that fills the chip, full-size tiles are the efficient form for the
         // down projection however few they are; the last one runs alone and follows the usual rule
-        const bool beside_big = (c + 1 < n) && !gateup_small && down_big_pays;
+        const bool beside_big = c + 1 < n;
         if (launch_gemm<momk::EPI_DOWN>(half[h], static_cast<const unsigned short*>(wd), nullptr, os + r0 * H, rows,
-                                        (int)H, (int)I, sb, nullptr, beside_big) != hipSuccess)
+                                        (int)H, (int)I, sb, beside_big) != hipSuccess)
             return MOM_ERR_HIP;
         if (hipEventRecord(ev[2 + h], sb) != hipSuccess) return MOM_ERR_HIP;
     }
@@ -268,12 +266,21 @@ int mom_mlp_prefill_pipelined(const void* x, const void* W_gate, const void* W_u
         if (!events[i]) return MOM_ERR_NULL;
         ev[i] = static_cast<hipEvent_t>(events[i]);
     }
-    // nothing to gain: a down projection that fills more than half of the CUs by itself was measured
-    // to run no faster beside the next gate/up kernel
+    // The two-stream schedule pays (measured) when the down projection of a mini-sequence leaves at least
+    // half of the CUs idle, the gate/up kernel beside it is one that fills the chip with 256-tiles, and the
+    // single round of long down tiles (K = I) does not outlast that kernel on the remaining CUs by more than
+    // half.  Otherwise this is the plain loop.  MOM_PIPELINE=1 in the environment forces the schedule (for
+    // tests, which need it on shapes of every size).
     const int cus = compute_units();
     if (cus <= 0) return MOM_ERR_HIP;
-    const int64_t tiles_dn = ((C + momk::kBM - 1) / momk::kBM) * ((H + momk::kBW - 1) / momk::kBW);
-    if (2 * tiles_dn > cus)
+    const int64_t tm = (C + momk::kBM - 1) / momk::kBM;
+    const int64_t tiles_dn = tm * ((H + momk::kBW - 1) / momk::kBW);
+    const int64_t tiles_gu = tm * ((I + momk::kBW / 2 - 1) / (momk::kBW / 2));
+    const int64_t cus_left = cus - tiles_dn > 0 ? cus - tiles_dn : 1;
+    const bool pays = 2 * tiles_dn <= cus && tiles_gu * 4 > (int64_t)cus * 3 &&
+                      2 * I <= 3 * ((tiles_gu + cus_left - 1) / cus_left) * H;
+    const char* force = getenv("MOM_PIPELINE");
+    if (!(force && force[0] == '1') && !pays)
         return mlp_driver(x, W_gate, W_up, W_down, S, H, I, mini_seq, out, workspace, workspace_bytes, stream,
                           nullptr, 0);
     return mlp_pipelined(x, W_gate, W_up, W_down, S, H, I, mini_seq, out, workspace, workspace_bytes,

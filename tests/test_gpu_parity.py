@@ -109,8 +109,11 @@ def test_ragged_shapes_match_oracle(S, H, I):
 
 
 @pytest.mark.parametrize("S,H,I", [(300, 96, 160), (257, 64, 64), (700, 384, 640), (1100, 256, 1024), (2500, 512, 512)])
-def test_pipelined_schedule_gives_the_same_bits(S, H, I):
-    """Two streams and a double-buffered workspace change the schedule, not one bit of the result."""
+def test_pipelined_schedule_gives_the_same_bits(S, H, I, monkeypatch):
+    """Two streams and a double-buffered workspace change the schedule, not one bit of the result.
+    (The library falls back to the plain loop where the schedule does not pay: MOM_PIPELINE=1
+    forces it, so that it is exercised on small shapes too.)"""
+    monkeypatch.setenv("MOM_PIPELINE", "1")
     dev = _dev()
     wl = synth.Workload("pipe", S=S, H=H, I=I, mini_seq=0, seed=S + 2 * I, w_std=0.05)
     xd, wgd, wud, wdd = (t.to(dev) for t in synth.mlp_inputs(wl))
@@ -524,17 +527,17 @@ def test_mistral_7b_448k_full_size():
 
 @pytest.mark.parametrize("S,H,I", [(257, 64, 64), (300, 128, 192), (700, 384, 640), (1100, 256, 1024)])
 def test_gemm_tile_forms_give_identical_bits(S, H, I, monkeypatch):
-    """The 256-tile form and the two 128-tile forms (shallow and deep LDS ring) of the four-wavefront
-    kernel - the library picks one by the number of tiles in a launch; MOM_GEMM_TILE overrides it -
-    agree bit for bit, with each other and across mini_seq, and match the oracle."""
+    """The forms of the four-wavefront kernel (tile edge 256 / 128 / 64, LDS ring of 5 / 10 / 20 slots) -
+    the library picks one by the number of tiles in a launch; MOM_GEMM_TILE overrides it - agree
+    bit for bit, with each other and across mini_seq, and match the oracle."""
     dev = _dev()
     wl = synth.Workload("tiles", S=S, H=H, I=I, mini_seq=0, seed=S + I, w_std=0.05)
     x, wg, wu, wd = synth.mlp_inputs(wl)
     ref = oracle.mlp_rows(*(synth.bits(t) for t in (x, wg, wu, wd)))
     xd, wgd, wud, wdd = (t.to(dev) for t in (x, wg, wu, wd))
     outs = []
-    for tile, C in (("256", 0), ("128deep", 0), ("128shallow", 0), ("256", 256), ("128shallow", 200),
-                    ("128deep", 100), ("128", 0), ("", 0)):
+    for tile, C in (("256", 0), ("128x10", 0), ("128x5", 0), ("64x5", 0), ("64x10", 0), ("64x20", 0), ("256", 256),
+                    ("128x5", 200), ("128x10", 100), ("64x20", 96), ("64x5", 300), ("128", 0), ("64", 0), ("", 0)):
         if tile:
             monkeypatch.setenv("MOM_GEMM_TILE", tile)
         else:
