@@ -123,7 +123,9 @@ hipError_t launch_gemv(const unsigned short* x, const unsigned short* Wa, const 
                        int64_t R, int64_t K, hipStream_t st) {
     const int rows_per_block = momk::kGemvWaves * (MODE == momk::MODE_GATEUP ? momk::kGemvStreams / 2 : (MODE == momk::MODE_DOWN ? 1 : momk::kGemvStreams));
     int64_t blocks = (R + rows_per_block - 1) / rows_per_block;
-    const int64_t max_blocks = 256 * 8;          // a few resident workgroups per CU; each loops over rows
+    // a few resident workgroups per CU, each looping over rows; the LM head, whose every wavefront keeps
+    // four 1 KiB row streams in flight, measured 5 % faster with 2 workgroups per CU than with 8
+    const int64_t max_blocks = (MODE == momk::MODE_LOGITS) ? 256 * 2 : 256 * 8;
     if (blocks > max_blocks) blocks = max_blocks;
     hipLaunchKernelGGL(momk::gemv_kernel<MODE>, dim3((unsigned)blocks), dim3(momk::kGemvWaves * 64),
                        (size_t)K * 2, st, x, Wa, Wb, y, (int)R, (int)K);
