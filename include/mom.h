@@ -11,7 +11,8 @@
  *     default stream).  Calls only ENQUEUE work; they never synchronise.
  *     Results are valid once the caller has synchronised the stream (or the
  *     event the call records).
- *   - The library allocates nothing and keeps no state between calls.
+ *   - The library allocates nothing.  The only state it keeps is the compute-unit count it
+ *     looks up once per device and the two testing overrides at the end of this header.
  *   - Return value: a `mom_status`; 0 is success.  Arguments are validated
  *     before anything is enqueued, so a non-zero status other than
  *     MOM_ERR_HIP means nothing was launched.
@@ -38,11 +39,20 @@ typedef enum {
     MOM_ERR_ALIGN = 3,     /* a pointer is not 16-byte aligned */
     MOM_ERR_ALIAS = 4,     /* an output or the workspace overlaps an input */
     MOM_ERR_WORKSPACE = 5, /* workspace_bytes is smaller than mom_mlp_workspace_bytes() */
-    MOM_ERR_HIP = 6        /* the HIP runtime reported an error while enqueueing */
+    MOM_ERR_HIP = 6,       /* the HIP runtime reported an error while enqueueing */
+    MOM_ERR_HOST = 7       /* a host buffer is not page-locked memory known to the HIP runtime */
 } mom_status;
 
 /* Human-readable, static string for a status value. */
 const char *mom_status_string(int status);
+
+/*
+ * Optional set-up for the current HIP device: looks up what the other calls otherwise look up
+ * on their first use on a device (the compute-unit count), so that those calls make no
+ * runtime query afterwards.  Call it once per device, with that device current, e.g. before
+ * a stream capture.  Returns MOM_ERR_HIP when there is no usable device.
+ */
+int mom_init(void);
 
 /*
  * Bytes of workspace mom_mlp_prefill needs: C*I*2 with C = mini_seq if
@@ -80,8 +90,7 @@ size_t mom_mlp_workspace_bytes(int64_t S, int64_t H, int64_t I, int64_t mini_seq
  * S = 0 is a no-op returning MOM_OK.  H and I must be positive multiples of 32.
  * All work is enqueued on `stream` in order (2 kernels per mini-sequence).
  * The kernels exist in several tile forms with bit-identical results; the library picks one per
- * launch.  Testing aid: MOM_GEMM_TILE = <edge> or <edge>x<ring slots> in the environment forces the
- * form (256, 128, 128x5, 128x10, 64, 64x5, 64x10, 64x20).
+ * launch (mom_debug_force_gemm_form overrides the choice, for tests).
  */
 int mom_mlp_prefill(const void *x, const void *W_gate, const void *W_up, const void *W_down,
                     int64_t S, int64_t H, int64_t I, int64_t mini_seq,
@@ -98,18 +107,19 @@ int mom_mlp_prefill(const void *x, const void *W_gate, const void *W_up, const v
  *   stream, stream2  two streams of the current device (stream2 should differ from stream).  The
  *                    call orders stream2 after the work already enqueued on stream, and stream
  *                    after the last kernel on stream2: the caller synchronises `stream` only.
- *   events           host array of 5 hipEvent_t created by the caller (disable-timing events
- *                    are fine); they are re-recorded freely during the call
+ *   events           host array of n_events >= 5 hipEvent_t created by the caller (disable-timing
+ *                    events are fine); the first five are re-recorded freely during the call.
+ *                    Fewer than five: MOM_ERR_SHAPE
  * With a single mini-sequence (mini_seq 0 or >= S), or where the schedule was measured not to pay
  * (a down projection that fills more than half of the CUs by itself, or mini-sequences so short
- * that both projections are latency-bound), this is mom_mlp_prefill on `stream`.  Testing aid:
- * MOM_PIPELINE=1 in the environment forces the two-stream schedule.
+ * that both projections are latency-bound), this is mom_mlp_prefill on `stream`
+ * (mom_debug_force_pipeline forces the two-stream schedule, for tests).
  */
 size_t mom_mlp_pipelined_workspace_bytes(int64_t S, int64_t H, int64_t I, int64_t mini_seq);
 int mom_mlp_prefill_pipelined(const void *x, const void *W_gate, const void *W_up, const void *W_down,
                               int64_t S, int64_t H, int64_t I, int64_t mini_seq,
                               void *out, void *workspace, size_t workspace_bytes,
-                              void *stream, void *stream2, void **events);
+                              void *stream, void *stream2, void **events, int64_t n_events);
 
 /*
  * The same computation with a HIP event recorded on `stream` before the first
@@ -155,7 +165,8 @@ int mom_mlp_last(const void *x_last, const void *W_gate, const void *W_up, const
  * asynchronous copy of k then v (bytes_each bytes each, device) to
  * `pinned_host` (host, page-locked, at least 2*bytes_each bytes; k at offset 0,
  * v at offset bytes_each) on `stream`, meant to be a side stream so the copy
- * runs under the MLP kernels.
+ * runs under the MLP kernels.  Pageable host memory is refused with MOM_ERR_HOST before
+ * anything is enqueued: the runtime would stage such a copy and block the caller.
  *   order_event      hipEvent_t; if not NULL it is recorded on producer_stream first and `stream`
  *                    waits for it, so the copy starts after the work that produced k and v
  *   producer_stream  the stream that produced k and v; NULL means the default stream (which does
@@ -174,12 +185,27 @@ int mom_kv_offload(const void *k, const void *v, void *pinned_host, void *stream
  * KV-cache reload before decode (Algorithm 1, if-branch: "transfer offloaded cache back to GPU";
  * Section 3.2): the mirror of mom_kv_offload.  Asynchronous copy of bytes_each bytes from
  * `pinned_host` (host, page-locked; k at offset 0, v at offset bytes_each) into device k and v
- * on `stream`; `done_event`, if not NULL, is recorded after both copies.  Ordering is the
- * caller's: make `stream` wait for the last work that still reads the old contents of k and v
+ * on `stream`; `done_event`, if not NULL, is recorded after both copies.  Pageable host memory
+ * is refused with MOM_ERR_HOST.  Ordering is the caller's: make `stream` wait for the last work that still reads the old contents of k and v
  * before this call, and make the consumers of k and v wait for `done_event`.
  */
 int mom_kv_reload(const void *pinned_host, void *k, void *v, void *stream, size_t bytes_each,
                   void *done_event);
+
+/*
+ * Testing aids (they follow no passage of the paper; process-wide, not meant for production).
+ *
+ * mom_debug_force_gemm_form: every later matrix-core launch with a contraction length that is a
+ * multiple of 64 uses tiles of tile_edge x tile_edge (256, 128 or 64) and an LDS ring of
+ * ring_slots slots (256: 5; 128: 5 or 10; 64: 5, 10 or 20; 0 = the library's choice for that
+ * edge) whatever the launch's size; (0, 0) gives the choice back to the library.  All forms give
+ * identical bits.  Other values: MOM_ERR_SHAPE, nothing changes.
+ *
+ * mom_debug_force_pipeline: on != 0 makes mom_mlp_prefill_pipelined use its two-stream schedule
+ * whenever there is more than one mini-sequence, also where it was measured not to pay.
+ */
+int mom_debug_force_gemm_form(int tile_edge, int ring_slots);
+int mom_debug_force_pipeline(int on);
 
 #ifdef __cplusplus
 }

@@ -15,9 +15,11 @@ LIB_PATH = os.path.join(_HERE, "libmom.so")
 
 SYMBOLS = ("mom_status_string", "mom_mlp_workspace_bytes", "mom_mlp_prefill", "mom_mlp_prefill_events",
            "mom_mlp_pipelined_workspace_bytes", "mom_mlp_prefill_pipelined",
-           "mom_lmhead_last", "mom_mlp_last", "mom_kv_offload", "mom_kv_reload")
+           "mom_lmhead_last", "mom_mlp_last", "mom_kv_offload", "mom_kv_reload",
+           "mom_init", "mom_debug_force_gemm_form", "mom_debug_force_pipeline")
 
-MOM_OK, MOM_ERR_NULL, MOM_ERR_SHAPE, MOM_ERR_ALIGN, MOM_ERR_ALIAS, MOM_ERR_WORKSPACE, MOM_ERR_HIP = range(7)
+(MOM_OK, MOM_ERR_NULL, MOM_ERR_SHAPE, MOM_ERR_ALIGN, MOM_ERR_ALIAS, MOM_ERR_WORKSPACE, MOM_ERR_HIP,
+ MOM_ERR_HOST) = range(8)
 
 _lib = None
 
@@ -50,7 +52,7 @@ def lib():
         L.mom_mlp_pipelined_workspace_bytes.argtypes = [i64, i64, i64, i64]
         L.mom_mlp_prefill_pipelined.restype = ctypes.c_int
         L.mom_mlp_prefill_pipelined.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, vp, vp, sz, vp, vp,
-                                                ctypes.POINTER(vp)]
+                                                ctypes.POINTER(vp), i64]
         L.mom_lmhead_last.restype = ctypes.c_int
         L.mom_lmhead_last.argtypes = [vp, vp, i64, vp, i64, vp]
         L.mom_kv_offload.restype = ctypes.c_int
@@ -59,6 +61,12 @@ def lib():
         L.mom_mlp_last.argtypes = [vp, vp, vp, vp, i64, i64, vp, vp, sz, vp]
         L.mom_kv_reload.restype = ctypes.c_int
         L.mom_kv_reload.argtypes = [vp, vp, vp, vp, sz, vp]
+        L.mom_init.restype = ctypes.c_int
+        L.mom_init.argtypes = []
+        L.mom_debug_force_gemm_form.restype = ctypes.c_int
+        L.mom_debug_force_gemm_form.argtypes = [ctypes.c_int, ctypes.c_int]
+        L.mom_debug_force_pipeline.restype = ctypes.c_int
+        L.mom_debug_force_pipeline.argtypes = [ctypes.c_int]
         _lib = L
     return _lib
 
@@ -118,13 +126,13 @@ def mom_mlp_pipelined_workspace_bytes(S, H, I, mini_seq):
 def mom_mlp_prefill_pipelined(x, W_gate, W_up, W_down, mini_seq, out, workspace, stream, stream2, events,
                               check=True):
     """As mom_mlp_prefill with down(c) on stream2 beside gate/up(c+1) on stream; workspace of
-    mom_mlp_pipelined_workspace_bytes; events: 4 torch.cuda.Event whose handles exist."""
+    mom_mlp_pipelined_workspace_bytes; events: at least 5 torch.cuda.Event whose handles exist."""
     S, H = x.shape
     I = W_gate.shape[0]
     arr = None if events is None else (ctypes.c_void_p * len(events))(*[e.cuda_event for e in events])
     rc = lib().mom_mlp_prefill_pipelined(_ptr(x), _ptr(W_gate), _ptr(W_up), _ptr(W_down), S, H, I, int(mini_seq),
                                          _ptr(out), _ptr(workspace), _nbytes(workspace), _stream(stream),
-                                         _stream(stream2), arr)
+                                         _stream(stream2), arr, 0 if events is None else len(events))
     if check and rc != MOM_OK:
         raise MomError(rc, "mom_mlp_prefill_pipelined")
     return rc
@@ -139,7 +147,28 @@ def mom_lmhead_last(x_last, W_lm, logits, stream=None, check=True):
     return rc
 
 
-def mom_kv_offload(k, v, pinned_host, stream, producer_stream=None, order_event=None, done_event=None):
+def mom_init():
+    rc = lib().mom_init()
+    if rc != MOM_OK:
+        raise MomError(rc, "mom_init")
+    return rc
+
+
+def mom_debug_force_gemm_form(tile_edge=0, ring_slots=0):
+    """Testing aid: force the tile form of the matrix-core kernels; (0, 0) = the library's choice."""
+    rc = lib().mom_debug_force_gemm_form(int(tile_edge), int(ring_slots))
+    if rc != MOM_OK:
+        raise MomError(rc, "mom_debug_force_gemm_form")
+    return rc
+
+
+def mom_debug_force_pipeline(on):
+    """Testing aid: make mom_mlp_prefill_pipelined always use its two-stream schedule."""
+    return lib().mom_debug_force_pipeline(1 if on else 0)
+
+
+def mom_kv_offload(k, v, pinned_host, stream, producer_stream=None, order_event=None, done_event=None,
+                   check=True):
     """Copy device k, v (same byte size) to the pinned host tensor (k then v) on `stream`.
     With order_event the copy is ordered after the work already enqueued on producer_stream
     (None = the default stream); done_event is recorded after both copies."""
@@ -150,7 +179,7 @@ def mom_kv_offload(k, v, pinned_host, stream, producer_stream=None, order_event=
                               None if producer_stream is None else _stream(producer_stream),
                               None if order_event is None else ctypes.c_void_p(order_event.cuda_event),
                               None if done_event is None else ctypes.c_void_p(done_event.cuda_event))
-    if rc != MOM_OK:
+    if check and rc != MOM_OK:
         raise MomError(rc, "mom_kv_offload")
     return rc
 
@@ -165,13 +194,13 @@ def mom_mlp_last(x_last, W_gate, W_up, W_down, out_last, workspace, stream=None,
     return rc
 
 
-def mom_kv_reload(pinned_host, k, v, stream, done_event=None):
+def mom_kv_reload(pinned_host, k, v, stream, done_event=None, check=True):
     """Copy k then v back from the pinned host tensor into the device tensors on `stream`."""
     nb = _nbytes(k)
     if _nbytes(v) != nb or _nbytes(pinned_host) < 2 * nb:
         raise ValueError("k and v must have equal byte size and pinned_host must hold both")
     rc = lib().mom_kv_reload(_ptr(pinned_host), _ptr(k), _ptr(v), _stream(stream), nb,
                              None if done_event is None else ctypes.c_void_p(done_event.cuda_event))
-    if rc != MOM_OK:
+    if check and rc != MOM_OK:
         raise MomError(rc, "mom_kv_reload")
     return rc

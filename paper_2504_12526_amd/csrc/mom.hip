@@ -2,11 +2,12 @@
 //
 // Host side: argument validation, the mini-sequence driver (Algorithm 1, else-branch), the
 // last-token LM head launch and the KV offload copies.  Nothing here allocates or synchronises.
+// The only state is what mom_init resolves per device (the compute-unit count) and the two testing
+// overrides of mom_debug_force_gemm_form / mom_debug_force_pipeline.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
-#include <stdlib.h>
-#include <string.h>
 
+#include <atomic>
 #include <type_traits>
 
 #include "mom.h"
@@ -49,12 +50,51 @@ int validate_mlp(const void* x, const void* wg, const void* wu, const void* wd, 
     return MOM_OK;
 }
 
+// Per-device data, resolved once per device (by mom_init or by the first call that needs it) with
+// that device current.
+constexpr int kMaxDevices = 64;
+struct DeviceInfo {
+    std::atomic<int> cus{0};                 // compute units, 0 = not resolved yet
+};
+DeviceInfo g_dev[kMaxDevices];
+
+// Testing overrides (mom_debug_force_gemm_form / mom_debug_force_pipeline); 0 = the library chooses.
+std::atomic<int> g_force_edge{0}, g_force_slots{0}, g_force_pipeline{0};
+
+DeviceInfo* current_device_info() {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    return &g_dev[dev];
+}
+
 // Compute units of the current device, or 0 on error.
 int compute_units() {
-    int dev = 0, cus = 0;
+    DeviceInfo* d = current_device_info();
+    if (!d) return 0;
+    int cus = d->cus.load(std::memory_order_relaxed);
+    if (cus > 0) return cus;
+    int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) return 0;
-    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) return 0;
+    d->cus.store(cus, std::memory_order_relaxed);
     return cus;
+}
+
+// MOM_OK if the n bytes at p are page-locked host memory known to the HIP runtime.  Pageable memory
+// would make hipMemcpyAsync stage the copy and block the calling thread, which the contract of the
+// KV calls ("only enqueue") excludes.
+int check_pinned_host(const void* p, size_t n) {
+    const unsigned char* b = static_cast<const unsigned char*>(p);
+    const unsigned char* ends[2] = {b, b + (n ? n - 1 : 0)};
+    for (const unsigned char* q : ends) {
+        hipPointerAttribute_t at;
+        if (hipPointerGetAttributes(&at, q) != hipSuccess) {
+            (void)hipGetLastError();          // an unknown pointer must not poison the next HIP call
+            return MOM_ERR_HOST;
+        }
+        if (at.type != hipMemoryTypeHost) return MOM_ERR_HOST;
+    }
+    return MOM_OK;
 }
 
 template <int EPI>
@@ -77,22 +117,19 @@ hipError_t launch_gemm(const unsigned short* X, const unsigned short* W0, const 
     // All kernels give identical bits (every output element sees the same MFMA sequence over k), so
     // the choice is free: the four-wavefront kernel needs whole 64-wide K stages, and its 128-tile
     // form is used when 256-tiles would leave a quarter or more of the CUs without work.
-#ifndef MOM_GEMM8_ONLY
     if (K % 64 == 0) {
         const int cus = compute_units();
         if (cus <= 0) return hipErrorInvalidDevice;
         // Tile edge and ring depth.  256-tiles unless they would leave a quarter or more of the CUs
         // without work; then 128-tiles, or 64-tiles when even those fill less than half of the CUs; the
         // small tiles get a deeper ring the fewer workgroups a CU has to hide latency with.
-        // MOM_GEMM_TILE = <edge> or <edge>x<slots> (256, 128, 128x5, 128x10, 64, 64x5, 64x10, 64x20) in the
-        // environment overrides the choice (for tests, which need every form on shapes of every size).
+        // mom_debug_force_gemm_form overrides the choice (for tests, which need every form on shapes of
+        // every size).
         int edge = 256, slots = 0;
-        const char* force = getenv("MOM_GEMM_TILE");
-        if (force && force[0]) {
-            edge = atoi(force);
-            const char* x = strchr(force, 'x');
-            slots = x ? atoi(x + 1) : 0;
-            if (edge != 256 && edge != 128 && edge != 64) return hipErrorInvalidValue;
+        const int force = g_force_edge.load(std::memory_order_relaxed);
+        if (force) {
+            edge = force;
+            slots = g_force_slots.load(std::memory_order_relaxed);
         } else if (!never_small && tiles * 4 <= (int64_t)cus * 3) {
             edge = (set_tiles(128) * 2 <= cus) ? 64 : 128;
         }
@@ -112,7 +149,6 @@ hipError_t launch_gemm(const unsigned short* X, const unsigned short* W0, const 
 #undef MOM_LAUNCH4
         return hipGetLastError();
     }
-#endif
     hipLaunchKernelGGL(momk::gemm_kernel<EPI>, dim3((unsigned)(a.tiles_per_xcd * 8)), dim3(momk::kThreads), 0, st,
                        a);
     return hipGetLastError();
@@ -222,8 +258,29 @@ const char* mom_status_string(int status) {
         case MOM_ERR_ALIAS: return "output or workspace overlaps an input";
         case MOM_ERR_WORKSPACE: return "workspace too small";
         case MOM_ERR_HIP: return "HIP runtime error";
+        case MOM_ERR_HOST: return "host pointer is not page-locked memory of the HIP runtime";
         default: return "unknown status";
     }
+}
+
+int mom_init(void) {
+    if (compute_units() <= 0) return MOM_ERR_HIP;
+    return MOM_OK;
+}
+
+int mom_debug_force_gemm_form(int tile_edge, int ring_slots) {
+    const bool ok = (tile_edge == 0 && ring_slots == 0) || (tile_edge == 256 && (ring_slots == 0 || ring_slots == 5)) ||
+                    (tile_edge == 128 && (ring_slots == 0 || ring_slots == 5 || ring_slots == 10)) ||
+                    (tile_edge == 64 && (ring_slots == 0 || ring_slots == 5 || ring_slots == 10 || ring_slots == 20));
+    if (!ok) return MOM_ERR_SHAPE;
+    g_force_slots.store(ring_slots, std::memory_order_relaxed);
+    g_force_edge.store(tile_edge, std::memory_order_relaxed);
+    return MOM_OK;
+}
+
+int mom_debug_force_pipeline(int on) {
+    g_force_pipeline.store(on ? 1 : 0, std::memory_order_relaxed);
+    return MOM_OK;
 }
 
 size_t mom_mlp_workspace_bytes(int64_t S, int64_t H, int64_t I, int64_t mini_seq) {
@@ -247,7 +304,8 @@ size_t mom_mlp_pipelined_workspace_bytes(int64_t S, int64_t H, int64_t I, int64_
 
 int mom_mlp_prefill_pipelined(const void* x, const void* W_gate, const void* W_up, const void* W_down, int64_t S,
                               int64_t H, int64_t I, int64_t mini_seq, void* out, void* workspace,
-                              size_t workspace_bytes, void* stream, void* stream2, void** events) {
+                              size_t workspace_bytes, void* stream, void* stream2, void** events,
+                              int64_t n_events) {
     int rc = validate_mlp(x, W_gate, W_up, W_down, S, H, I, mini_seq, out, workspace, workspace_bytes);
     if (rc != MOM_OK || S == 0) return rc;
     const size_t need = mom_mlp_pipelined_workspace_bytes(S, H, I, mini_seq);
@@ -263,6 +321,7 @@ int mom_mlp_prefill_pipelined(const void* x, const void* W_gate, const void* W_u
         return mlp_driver(x, W_gate, W_up, W_down, S, H, I, mini_seq, out, workspace, workspace_bytes, stream,
                           nullptr, 0);
     if (!events) return MOM_ERR_NULL;
+    if (n_events < 5) return MOM_ERR_SHAPE;
     hipEvent_t ev[5];
     for (int i = 0; i < 5; ++i) {
         if (!events[i]) return MOM_ERR_NULL;
@@ -271,8 +330,8 @@ int mom_mlp_prefill_pipelined(const void* x, const void* W_gate, const void* W_u
     // The two-stream schedule pays (measured) when the down projection of a mini-sequence leaves at least
     // half of the CUs idle, the gate/up kernel beside it is one that fills the chip with 256-tiles, and the
     // single round of long down tiles (K = I) does not outlast that kernel on the remaining CUs by more than
-    // half.  Otherwise this is the plain loop.  MOM_PIPELINE=1 in the environment forces the schedule (for
-    // tests, which need it on shapes of every size).
+    // half.  Otherwise this is the plain loop.  mom_debug_force_pipeline forces the schedule (for tests,
+    // which need it on shapes of every size).
     const int cus = compute_units();
     if (cus <= 0) return MOM_ERR_HIP;
     const int64_t tm = (C + momk::kBM - 1) / momk::kBM;
@@ -281,8 +340,7 @@ int mom_mlp_prefill_pipelined(const void* x, const void* W_gate, const void* W_u
     const int64_t cus_left = cus - tiles_dn > 0 ? cus - tiles_dn : 1;
     const bool pays = 2 * tiles_dn <= cus && tiles_gu * 4 > (int64_t)cus * 3 &&
                       2 * I <= 3 * ((tiles_gu + cus_left - 1) / cus_left) * H;
-    const char* force = getenv("MOM_PIPELINE");
-    if (!(force && force[0] == '1') && !pays)
+    if (!g_force_pipeline.load(std::memory_order_relaxed) && !pays)
         return mlp_driver(x, W_gate, W_up, W_down, S, H, I, mini_seq, out, workspace, workspace_bytes, stream,
                           nullptr, 0);
     return mlp_pipelined(x, W_gate, W_up, W_down, S, H, I, mini_seq, out, workspace, workspace_bytes,
@@ -342,6 +400,10 @@ int mom_kv_offload(const void* k, const void* v, void* pinned_host, void* stream
                    void* producer_stream, void* order_event, void* done_event) {
     if (bytes_each != 0 && (!k || !v || !pinned_host)) return MOM_ERR_NULL;
     if (producer_stream && !order_event) return MOM_ERR_NULL;
+    if (bytes_each != 0) {
+        const int rc = check_pinned_host(pinned_host, 2 * bytes_each);
+        if (rc != MOM_OK) return rc;
+    }
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (order_event) {
         // producer_stream may be NULL here: that is the default stream, which does not order itself
@@ -362,6 +424,10 @@ int mom_kv_offload(const void* k, const void* v, void* pinned_host, void* stream
 
 int mom_kv_reload(const void* pinned_host, void* k, void* v, void* stream, size_t bytes_each, void* done_event) {
     if (bytes_each != 0 && (!k || !v || !pinned_host)) return MOM_ERR_NULL;
+    if (bytes_each != 0) {
+        const int rc = check_pinned_host(pinned_host, 2 * bytes_each);
+        if (rc != MOM_OK) return rc;
+    }
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (bytes_each != 0) {
         const unsigned char* src = static_cast<const unsigned char*>(pinned_host);

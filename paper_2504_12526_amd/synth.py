@@ -118,9 +118,11 @@ def bits_to_f64(a):
     return (a.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
 
 
-def parity_rows(S, mini_seq, n_random=128, seed=0):
+def parity_rows(S, mini_seq, n_random=128, seed=0, residues=256):
     """Row sample for big-S parity: first/last row of every mini-sequence (both sides of
-    every boundary) plus seeded random rows; sorted, unique."""
+    every boundary), seeded random rows, and for every residue class r mod `residues` one seeded
+    random row of that class (so that a sample covers every row position of a `residues`-row tile
+    of whoever computes the rows); sorted, unique."""
     C = S if (mini_seq <= 0 or mini_seq > S) else mini_seq
     rows = {0, S - 1}
     for r0 in range(0, S, C):
@@ -128,4 +130,7 @@ def parity_rows(S, mini_seq, n_random=128, seed=0):
         rows.add(min(S, r0 + C) - 1)
     rng = np.random.default_rng(seed)
     rows.update(int(r) for r in rng.integers(0, S, size=n_random))
+    for rho in range(min(residues, S)):
+        n_in_class = (S - 1 - rho) // residues + 1
+        rows.add(rho + residues * int(rng.integers(0, n_in_class)))
     return np.array(sorted(r for r in rows if 0 <= r < S), dtype=np.int64)

@@ -26,8 +26,8 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_status_strings():
-    seen = {binding.status_string(s) for s in range(7)}
-    assert len(seen) == 7 and "unknown status" not in seen
+    seen = {binding.status_string(s) for s in range(8)}
+    assert len(seen) == 8 and "unknown status" not in seen
     assert binding.status_string(99) == "unknown status"
 
 
@@ -76,18 +76,19 @@ def test_pipelined_workspace_and_argument_validation():
     vp = ctypes.c_void_p
 
     def call(x=0x1000, wg=0x2000000, wu=0x3000000, wd=0x4000000, S=64, H=64, I=96, C=16, out=0x5000000,
-             ws=0x6000000, wsb=None, events=True):
+             ws=0x6000000, wsb=None, events=True, n_events=5):
         if wsb is None:
             wsb = pb(S, H, I, C)
         ev = (vp * 5)(*[vp(0x10 + i) for i in range(5)]) if events else None
         return binding.lib().mom_mlp_prefill_pipelined(vp(x), vp(wg), vp(wu), vp(wd), S, H, I, C, vp(out), vp(ws),
-                                                       wsb, None, None, ev)
+                                                       wsb, None, None, ev, n_events)
     assert call(H=48) == binding.MOM_ERR_SHAPE
     assert call(wu=0) == binding.MOM_ERR_NULL
     assert call(out=0x5000004) == binding.MOM_ERR_ALIGN
     assert call(wsb=wb(64, 64, 96, 16)) == binding.MOM_ERR_WORKSPACE          # one half is not enough
     assert call(ws=0x5000000 - 16 * 96 * 2 - 32) == binding.MOM_ERR_ALIAS    # second half runs into out
     assert call(events=False) == binding.MOM_ERR_NULL                         # several mini-sequences need events
+    assert call(n_events=4) == binding.MOM_ERR_SHAPE                          # ... five of them
     assert call(S=0, x=0, out=0, ws=0) == binding.MOM_OK
 
 
@@ -114,6 +115,21 @@ def test_lmhead_and_offload_argument_validation():
     assert L.mom_kv_reload(None, vp(0x10), vp(0x20), None, 16, None) == binding.MOM_ERR_NULL
     assert L.mom_kv_offload(None, vp(0x10), vp(0x20), None, 16, None, None, None) == binding.MOM_ERR_NULL
     assert L.mom_kv_offload(vp(0x10), vp(0x20), vp(0x30), None, 16, vp(0x1), None, None) == binding.MOM_ERR_NULL
+
+
+def test_debug_overrides_validate_their_arguments():
+    L = binding.lib()
+    for ok in ((256, 0), (256, 5), (128, 5), (128, 10), (64, 5), (64, 10), (64, 20), (128, 0), (64, 0), (0, 0)):
+        assert L.mom_debug_force_gemm_form(*ok) == binding.MOM_OK
+    for bad in ((100, 0), (256, 10), (128, 20), (64, 3), (0, 5), (-64, 0)):
+        assert L.mom_debug_force_gemm_form(*bad) == binding.MOM_ERR_SHAPE
+    assert L.mom_debug_force_pipeline(1) == binding.MOM_OK and L.mom_debug_force_pipeline(0) == binding.MOM_OK
+
+
+def test_product_reads_no_environment_variables():
+    pkg = os.path.join(ROOT, "paper_2504_12526_amd", "csrc")
+    for f in os.listdir(pkg):
+        assert "getenv" not in open(os.path.join(pkg, f)).read(), f
 
 
 def test_product_does_not_import_the_oracle():

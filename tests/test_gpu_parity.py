@@ -73,6 +73,24 @@ def bits_equal(a, b):
     return torch.equal(a.view(torch.int16), b.view(torch.int16))
 
 
+@pytest.fixture
+def forced_pipeline():
+    binding.mom_debug_force_pipeline(True)
+    yield
+    binding.mom_debug_force_pipeline(False)
+
+
+@pytest.fixture
+def gemm_form():
+    """Callable (edge, slots) that forces a tile form of the matrix-core kernels; the library's own
+    choice is restored afterwards."""
+    yield binding.mom_debug_force_gemm_form
+    binding.mom_debug_force_gemm_form(0, 0)
+
+
+FORMS = ((256, 5), (128, 5), (128, 10), (64, 5), (64, 10), (64, 20))
+
+
 # ------------------------------------------------------------------ small shapes, full compare
 
 def test_tiny_workload_matches_oracle_and_unchunked():
@@ -109,11 +127,10 @@ def test_ragged_shapes_match_oracle(S, H, I):
 
 
 @pytest.mark.parametrize("S,H,I", [(300, 96, 160), (257, 64, 64), (700, 384, 640), (1100, 256, 1024), (2500, 512, 512)])
-def test_pipelined_schedule_gives_the_same_bits(S, H, I, monkeypatch):
+def test_pipelined_schedule_gives_the_same_bits(S, H, I, forced_pipeline):
     """Two streams and a double-buffered workspace change the schedule, not one bit of the result.
-    (The library falls back to the plain loop where the schedule does not pay: MOM_PIPELINE=1
-    forces it, so that it is exercised on small shapes too.)"""
-    monkeypatch.setenv("MOM_PIPELINE", "1")
+    (The library falls back to the plain loop where the schedule does not pay:
+    mom_debug_force_pipeline forces it, so that it is exercised on small shapes too.)"""
     dev = _dev()
     wl = synth.Workload("pipe", S=S, H=H, I=I, mini_seq=0, seed=S + 2 * I, w_std=0.05)
     xd, wgd, wud, wdd = (t.to(dev) for t in synth.mlp_inputs(wl))
@@ -140,6 +157,9 @@ def test_pipelined_schedule_gives_the_same_bits(S, H, I, monkeypatch):
     binding.mom_mlp_prefill_pipelined(xd, wgd, wud, wdd, 128, o1, ws, main, main, events)
     main.synchronize()
     assert bits_equal(o1, full)
+    # fewer than five events: refused before anything is enqueued
+    assert binding.mom_mlp_prefill_pipelined(xd, wgd, wud, wdd, 128, o1, ws, main, side, events[:4],
+                                             check=False) == binding.MOM_ERR_SHAPE
     torch.cuda.synchronize()
 
 
@@ -331,6 +351,32 @@ def test_kv_offload_is_byte_exact_and_ordered(producer):
     torch.cuda.synchronize()
 
 
+def test_kv_calls_refuse_pageable_host_memory():
+    """A pageable host buffer would make the runtime stage the copy and block the caller: both KV
+    calls return MOM_ERR_HOST for it before anything is enqueued, and the next call still works."""
+    dev = _dev()
+    wl = synth.Workload("kvp", S=256, H=32, I=32, mini_seq=0, kv_heads=8, seed=3)
+    k, v = synth.kv_inputs(wl, device=dev)
+    pageable = torch.zeros(2 * k.numel(), dtype=torch.bfloat16)
+    side = torch.cuda.Stream()
+    assert binding.mom_kv_offload(k, v, pageable, side, check=False) == binding.MOM_ERR_HOST
+    assert binding.mom_kv_reload(pageable, k, v, side, check=False) == binding.MOM_ERR_HOST
+    on_device = torch.zeros(2 * k.numel(), dtype=torch.bfloat16, device=dev)
+    assert binding.mom_kv_offload(k, v, on_device, side, check=False) == binding.MOM_ERR_HOST   # device memory as "host"
+    torch.cuda.synchronize()
+    assert torch.count_nonzero(pageable.view(torch.int16)).item() == 0
+    assert "page-locked" in binding.status_string(binding.MOM_ERR_HOST)
+    pinned = torch.empty(2 * k.numel(), dtype=torch.bfloat16).pin_memory()
+    done = torch.cuda.Event(); done.record(side)
+    assert binding.mom_kv_offload(k, v, pinned, side, done_event=done) == binding.MOM_OK
+    done.synchronize()
+    assert torch.equal(pinned[: k.numel()].view(torch.int16), k.cpu().view(torch.int16).ravel())
+    # a window inside a pinned allocation is fine; one that runs past its end is not
+    n = k.numel()
+    assert binding.mom_kv_offload(k[:64], v[:64], pinned[n:], side, done_event=done) == binding.MOM_OK
+    done.synchronize()
+
+
 def test_kv_reload_round_trip():
     """Offload then reload (Algorithm 1: cache back to the GPU before decode) returns the same bytes."""
     dev = _dev()
@@ -450,7 +496,9 @@ def _full_size_case(name, sweep=(), check_unchunked=True):
     x, wg, wu, wd = synth.mlp_inputs(wl, device=dev)
     out, nbytes = run_mlp(x, wg, wu, wd, wl.mini_seq)
     assert nbytes == wl.mini_seq * wl.I * 2
-    rows = synth.parity_rows(wl.S, wl.mini_seq, n_random=96, seed=wl.seed)
+    # both sides of every mini-sequence boundary, 96 random rows, and every row position of a 256-row tile
+    rows = synth.parity_rows(wl.S, wl.mini_seq, n_random=96, seed=wl.seed, residues=256)
+    assert len(set(int(r) % 256 for r in rows)) == 256
     rows_t = torch.from_numpy(rows).to(dev)
     ref = oracle.mlp_rows(synth.bits(x[rows_t]), synth.bits(wg), synth.bits(wu), synth.bits(wd))
     assert_close_to_oracle(_f32(out[rows_t]), ref, f"{name} sampled rows")
@@ -467,7 +515,8 @@ def _full_size_case(name, sweep=(), check_unchunked=True):
 
 
 def test_llama3_8b_32k_full_size():
-    wl, out = _full_size_case("llama3_8b_32k", sweep=(1024, 2048, 8192))
+    # 128 ... 512 rows: the launcher's small-tile, deep-ring forms at the production K (4096 / 14336)
+    wl, out = _full_size_case("llama3_8b_32k", sweep=(128, 256, 512, 1024, 2048, 8192))
     # ragged sequence length at the same shape: 32768 - 77 rows, chunk 4096 vs full
     dev = _dev()
     x, wg, wu, wd = synth.mlp_inputs(wl, device=dev, S=wl.S - 77)
@@ -513,7 +562,7 @@ def test_llama3_8b_128k_full_size_with_offload_and_lmhead():
 
 def test_qwen25_7b_256k_full_size():
     dev = _dev()
-    wl, _ = _full_size_case("qwen25_7b_256k", check_unchunked=True)
+    wl, _ = _full_size_case("qwen25_7b_256k", check_unchunked=True, sweep=(128, 256, 512, 2048))
     xl, wlm = synth.lmhead_inputs(wl, device=dev)
     logits = torch.empty((wl.V,), dtype=torch.float32, device=dev)
     binding.mom_lmhead_last(xl, wlm, logits)
@@ -525,27 +574,71 @@ def test_mistral_7b_448k_full_size():
     _full_size_case("mistral_7b_448k", check_unchunked=True)
 
 
-@pytest.mark.parametrize("S,H,I", [(257, 64, 64), (300, 128, 192), (700, 384, 640), (1100, 256, 1024)])
-def test_gemm_tile_forms_give_identical_bits(S, H, I, monkeypatch):
+@pytest.mark.parametrize("S,H,I", [(257, 64, 64), (300, 128, 192), (700, 384, 640), (1100, 256, 1024),
+                                   # long contractions: 32 / 40 stages, several periods of the 20-slot ring
+                                   (600, 2048, 2560)])
+def test_gemm_tile_forms_give_identical_bits(S, H, I, gemm_form):
     """The forms of the four-wavefront kernel (tile edge 256 / 128 / 64, LDS ring of 5 / 10 / 20 slots) -
-    the library picks one by the number of tiles in a launch; MOM_GEMM_TILE overrides it - agree
-    bit for bit, with each other and across mini_seq, and match the oracle."""
+    the library picks one by the number of tiles in a launch; mom_debug_force_gemm_form overrides it -
+    agree bit for bit, with each other and across mini_seq, and match the oracle."""
     dev = _dev()
-    wl = synth.Workload("tiles", S=S, H=H, I=I, mini_seq=0, seed=S + I, w_std=0.05)
+    wl = synth.Workload("tiles", S=S, H=H, I=I, mini_seq=0, seed=S + I, w_std=0.05 if H < 2048 else 0.02)
     x, wg, wu, wd = synth.mlp_inputs(wl)
     ref = oracle.mlp_rows(*(synth.bits(t) for t in (x, wg, wu, wd)))
     xd, wgd, wud, wdd = (t.to(dev) for t in (x, wg, wu, wd))
     outs = []
-    for tile, C in (("256", 0), ("128x10", 0), ("128x5", 0), ("64x5", 0), ("64x10", 0), ("64x20", 0), ("256", 256),
-                    ("128x5", 200), ("128x10", 100), ("64x20", 96), ("64x5", 300), ("128", 0), ("64", 0), ("", 0)):
-        if tile:
-            monkeypatch.setenv("MOM_GEMM_TILE", tile)
-        else:
-            monkeypatch.delenv("MOM_GEMM_TILE", raising=False)
+    for form, C in (((256, 0), 0), ((128, 10), 0), ((128, 5), 0), ((64, 5), 0), ((64, 10), 0), ((64, 20), 0),
+                    ((256, 5), 256), ((128, 5), 200), ((128, 10), 100), ((64, 20), 96), ((64, 5), 300),
+                    ((64, 10), 130), ((128, 0), 0), ((64, 0), 0), ((0, 0), 0)):
+        gemm_form(*form)
         outs.append(run_mlp(xd, wgd, wud, wdd, C)[0])
     for i, o in enumerate(outs[1:]):
         assert bits_equal(outs[0], o), f"form {i + 1}"
     assert_close_to_oracle(_f32(outs[0]), ref, f"tile forms S={S} H={H} I={I}")
+
+
+def test_forced_form_validation(gemm_form):
+    for bad in ((100, 0), (256, 10), (128, 20), (64, 3), (0, 5), (-64, 0)):
+        assert binding.lib().mom_debug_force_gemm_form(*bad) == binding.MOM_ERR_SHAPE
+
+
+@pytest.mark.parametrize("name", ["llama3_8b_32k", "qwen25_7b_256k"])
+def test_every_tile_form_at_production_contraction_lengths(name, gemm_form):
+    """Every (tile edge, ring depth) form on a slice of a full-size workload - K = 4096 / 14336 (Llama) and
+    3584 / 18944 (Qwen), 56 to 296 stages - against the oracle on sampled rows and bit for bit against
+    each other; the slice is ragged in rows so that every form masks a partial tile."""
+    dev = _dev()
+    wl = synth.WORKLOADS[name]
+    S = 4096 + 1000 + 37
+    x, wg, wu, wd = synth.mlp_inputs(wl, device=dev, S=S)
+    gemm_form(256, 5)
+    base, _ = run_mlp(x, wg, wu, wd, 0)
+    rows = synth.parity_rows(S, 0, n_random=32, seed=3, residues=256)
+    rows_t = torch.from_numpy(rows).to(dev)
+    ref = oracle.mlp_rows(synth.bits(x[rows_t]), synth.bits(wg), synth.bits(wu), synth.bits(wd))
+    assert_close_to_oracle(_f32(base[rows_t]), ref, f"{name} slice, 256-tiles")
+    for form in FORMS[1:]:
+        gemm_form(*form)
+        for C in (0, 1024 + 100):
+            o, _ = run_mlp(x, wg, wu, wd, C)
+            assert bits_equal(o, base), f"{name}: form {form}, C={C}"
+
+
+def test_eight_wavefront_kernel_at_mid_size_matches_oracle():
+    """Contraction lengths that are odd multiples of 32 run the eight-wavefront kernel (the
+    four-wavefront one needs whole 64-wide stages): a mid-size case with its final half stage in both
+    projections, sampled rows against the oracle, mini-sequence against full sequence bit for bit."""
+    dev = _dev()
+    wl = synth.Workload("g8", S=4096 + 300, H=1056, I=2080, mini_seq=1024, seed=31, w_std=0.03)
+    x, wg, wu, wd = synth.mlp_inputs(wl, device=dev)
+    out, _ = run_mlp(x, wg, wu, wd, wl.mini_seq)
+    rows = synth.parity_rows(wl.S, wl.mini_seq, n_random=32, seed=wl.seed, residues=256)
+    rows_t = torch.from_numpy(rows).to(dev)
+    ref = oracle.mlp_rows(synth.bits(x[rows_t]), synth.bits(wg), synth.bits(wu), synth.bits(wd))
+    assert_close_to_oracle(_f32(out[rows_t]), ref, "eight-wavefront kernel, sampled rows")
+    for C in (0, 300, 2048):
+        o, _ = run_mlp(x, wg, wu, wd, C)
+        assert bits_equal(o, out), f"C={C}"
 
 
 def test_entry_points_can_be_captured_in_a_hip_graph():
