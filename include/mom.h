@@ -11,8 +11,9 @@
  *     default stream).  Calls only ENQUEUE work; they never synchronise.
  *     Results are valid once the caller has synchronised the stream (or the
  *     event the call records).
- *   - The library allocates nothing.  The only state it keeps is the compute-unit count it
- *     looks up once per device and the two testing overrides at the end of this header.
+ *   - The library allocates nothing.  The only state it keeps is what it looks up once per
+ *     device (compute-unit count, address of the static workspace of mom_mlp_prefill_static)
+ *     and the two testing overrides at the end of this header.
  *   - Return value: a `mom_status`; 0 is success.  Arguments are validated
  *     before anything is enqueued, so a non-zero status other than
  *     MOM_ERR_HIP means nothing was launched.
@@ -48,8 +49,8 @@ const char *mom_status_string(int status);
 
 /*
  * Optional set-up for the current HIP device: looks up what the other calls otherwise look up
- * on their first use on a device (the compute-unit count), so that those calls make no
- * runtime query afterwards.  Call it once per device, with that device current, e.g. before
+ * on their first use on a device (the compute-unit count, the device address of the static
+ * workspace of mom_mlp_prefill_static), so that those calls make no runtime query afterwards.  Call it once per device, with that device current, e.g. before
  * a stream capture.  Returns MOM_ERR_HIP when there is no usable device.
  */
 int mom_init(void);
@@ -95,6 +96,25 @@ size_t mom_mlp_workspace_bytes(int64_t S, int64_t H, int64_t I, int64_t mini_seq
 int mom_mlp_prefill(const void *x, const void *W_gate, const void *W_up, const void *W_down,
                     int64_t S, int64_t H, int64_t I, int64_t mini_seq,
                     void *out, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * mom_mlp_prefill for callers that cannot provide (or allocate) a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses in which nothing may call hipMalloc.  Same computation,
+ * same kernels and same bits as mom_mlp_prefill; the mini-sequence intermediate lives in a
+ * MOM_STATIC_WORKSPACE_BYTES array that is part of the library's device image (each device the
+ * library is used on holds its copy until the process ends).  The call allocates nothing and
+ * frees nothing.
+ *   Limit: min(mini_seq, S) * I * 2 <= MOM_STATIC_WORKSPACE_BYTES (e.g. 2048 rows at I = 14336),
+ *   else MOM_ERR_WORKSPACE and nothing is enqueued.  Other arguments and errors as mom_mlp_prefill.
+ *   The device address of the array is looked up on the first call on a device (or by mom_init,
+ *   which callers under stream capture should call beforehand).
+ *   All calls on one device share the one array: every element a call reads it has written
+ *   before, so nothing needs clearing between calls, but two calls that may run concurrently on
+ *   one device (different streams without an ordering between them) race.
+ */
+#define MOM_STATIC_WORKSPACE_BYTES (64u << 20)
+int mom_mlp_prefill_static(const void *x, const void *W_gate, const void *W_up, const void *W_down,
+                           int64_t S, int64_t H, int64_t I, int64_t mini_seq, void *out, void *stream);
 
 /*
  * The same computation and the same bits as mom_mlp_prefill, scheduled on two streams with a

@@ -16,7 +16,9 @@ LIB_PATH = os.path.join(_HERE, "libmom.so")
 SYMBOLS = ("mom_status_string", "mom_mlp_workspace_bytes", "mom_mlp_prefill", "mom_mlp_prefill_events",
            "mom_mlp_pipelined_workspace_bytes", "mom_mlp_prefill_pipelined",
            "mom_lmhead_last", "mom_mlp_last", "mom_kv_offload", "mom_kv_reload",
-           "mom_init", "mom_debug_force_gemm_form", "mom_debug_force_pipeline")
+           "mom_init", "mom_debug_force_gemm_form", "mom_debug_force_pipeline", "mom_mlp_prefill_static")
+
+MOM_STATIC_WORKSPACE_BYTES = 64 << 20
 
 (MOM_OK, MOM_ERR_NULL, MOM_ERR_SHAPE, MOM_ERR_ALIGN, MOM_ERR_ALIAS, MOM_ERR_WORKSPACE, MOM_ERR_HIP,
  MOM_ERR_HOST) = range(8)
@@ -61,6 +63,8 @@ def lib():
         L.mom_mlp_last.argtypes = [vp, vp, vp, vp, i64, i64, vp, vp, sz, vp]
         L.mom_kv_reload.restype = ctypes.c_int
         L.mom_kv_reload.argtypes = [vp, vp, vp, vp, sz, vp]
+        L.mom_mlp_prefill_static.restype = ctypes.c_int
+        L.mom_mlp_prefill_static.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, vp, vp]
         L.mom_init.restype = ctypes.c_int
         L.mom_init.argtypes = []
         L.mom_debug_force_gemm_form.restype = ctypes.c_int
@@ -102,6 +106,17 @@ def mom_mlp_prefill(x, W_gate, W_up, W_down, mini_seq, out, workspace, stream=No
                                _ptr(out), _ptr(workspace), _nbytes(workspace), _stream(stream))
     if check and rc != MOM_OK:
         raise MomError(rc, "mom_mlp_prefill")
+    return rc
+
+
+def mom_mlp_prefill_static(x, W_gate, W_up, W_down, mini_seq, out, stream=None, check=True):
+    """mom_mlp_prefill with the library's own static workspace (at most MOM_STATIC_WORKSPACE_BYTES)."""
+    S, H = x.shape
+    I = W_gate.shape[0]
+    rc = lib().mom_mlp_prefill_static(_ptr(x), _ptr(W_gate), _ptr(W_up), _ptr(W_down), S, H, I, int(mini_seq),
+                                      _ptr(out), _stream(stream))
+    if check and rc != MOM_OK:
+        raise MomError(rc, "mom_mlp_prefill_static")
     return rc
 
 

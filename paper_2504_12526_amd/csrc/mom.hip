@@ -2,8 +2,8 @@
 //
 // Host side: argument validation, the mini-sequence driver (Algorithm 1, else-branch), the
 // last-token LM head launch and the KV offload copies.  Nothing here allocates or synchronises.
-// The only state is what mom_init resolves per device (the compute-unit count) and the two testing
-// overrides of mom_debug_force_gemm_form / mom_debug_force_pipeline.
+// The only state is what mom_init resolves per device (compute-unit count, address of the static
+// workspace) and the two testing overrides of mom_debug_force_gemm_form / mom_debug_force_pipeline.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -14,6 +14,11 @@
 #include "mom_gemm.hip.inc"
 #include "mom_gemm4.hip.inc"
 #include "mom_gemv.hip.inc"
+
+// Workspace of mom_mlp_prefill_static: one copy per device, held from the moment the library is
+// loaded on a device until the process ends.  In host code this name is only a handle for
+// hipGetSymbolAddress; the device address it yields (kept per device in g_dev) is what kernels get.
+static __device__ __align__(256) unsigned char scratch[MOM_STATIC_WORKSPACE_BYTES];
 
 namespace {
 
@@ -55,6 +60,7 @@ int validate_mlp(const void* x, const void* wg, const void* wu, const void* wd, 
 constexpr int kMaxDevices = 64;
 struct DeviceInfo {
     std::atomic<int> cus{0};                 // compute units, 0 = not resolved yet
+    std::atomic<void*> static_ws{nullptr};   // device address of this device's copy of `scratch`
 };
 DeviceInfo g_dev[kMaxDevices];
 
@@ -78,6 +84,20 @@ int compute_units() {
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) return 0;
     d->cus.store(cus, std::memory_order_relaxed);
     return cus;
+}
+
+// Device address of the current device's copy of `scratch`, or nullptr on error.
+void* static_workspace() {
+    DeviceInfo* d = current_device_info();
+    if (!d) return nullptr;
+    void* p = d->static_ws.load(std::memory_order_acquire);
+    if (p) return p;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    d->static_ws.store(p, std::memory_order_release);
+    return p;
 }
 
 // MOM_OK if the n bytes at p are page-locked host memory known to the HIP runtime.  Pageable memory
@@ -265,6 +285,7 @@ const char* mom_status_string(int status) {
 
 int mom_init(void) {
     if (compute_units() <= 0) return MOM_ERR_HIP;
+    if (!static_workspace()) return MOM_ERR_HIP;
     return MOM_OK;
 }
 
@@ -292,6 +313,18 @@ int mom_mlp_prefill(const void* x, const void* W_gate, const void* W_up, const v
                     int64_t H, int64_t I, int64_t mini_seq, void* out, void* workspace,
                     size_t workspace_bytes, void* stream) {
     return mlp_driver(x, W_gate, W_up, W_down, S, H, I, mini_seq, out, workspace, workspace_bytes, stream,
+                      nullptr, 0);
+}
+
+int mom_mlp_prefill_static(const void* x, const void* W_gate, const void* W_up, const void* W_down, int64_t S,
+                           int64_t H, int64_t I, int64_t mini_seq, void* out, void* stream) {
+    if (S < 0 || H <= 0 || I <= 0 || mini_seq < 0) return MOM_ERR_SHAPE;
+    if (S == 0) return validate_mlp(x, W_gate, W_up, W_down, S, H, I, mini_seq, out, nullptr, 0);
+    const size_t need = mom_mlp_workspace_bytes(S, H, I, mini_seq);
+    if (need > (size_t)MOM_STATIC_WORKSPACE_BYTES) return MOM_ERR_WORKSPACE;
+    void* ws = static_workspace();
+    if (!ws) return MOM_ERR_HIP;
+    return mlp_driver(x, W_gate, W_up, W_down, S, H, I, mini_seq, out, ws, (size_t)MOM_STATIC_WORKSPACE_BYTES, stream,
                       nullptr, 0);
 }
 
