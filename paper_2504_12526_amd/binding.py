@@ -16,7 +16,8 @@ LIB_PATH = os.path.join(_HERE, "libmom.so")
 SYMBOLS = ("mom_status_string", "mom_mlp_workspace_bytes", "mom_mlp_prefill", "mom_mlp_prefill_events",
            "mom_mlp_pipelined_workspace_bytes", "mom_mlp_prefill_pipelined",
            "mom_lmhead_last", "mom_mlp_last", "mom_kv_offload", "mom_kv_reload",
-           "mom_init", "mom_debug_force_gemm_form", "mom_debug_force_pipeline", "mom_mlp_prefill_static")
+           "mom_init", "mom_debug_force_gemm_form", "mom_debug_force_pipeline", "mom_mlp_prefill_static",
+           "mom_debug_mfma_probe")
 
 MOM_STATIC_WORKSPACE_BYTES = 64 << 20
 
@@ -69,6 +70,8 @@ def lib():
         L.mom_init.argtypes = []
         L.mom_debug_force_gemm_form.restype = ctypes.c_int
         L.mom_debug_force_gemm_form.argtypes = [ctypes.c_int, ctypes.c_int]
+        L.mom_debug_mfma_probe.restype = ctypes.c_int
+        L.mom_debug_mfma_probe.argtypes = [vp, sz, vp, sz, i64, ctypes.c_int, vp, vp]
         L.mom_debug_force_pipeline.restype = ctypes.c_int
         L.mom_debug_force_pipeline.argtypes = [ctypes.c_int]
         _lib = L
@@ -180,6 +183,18 @@ def mom_debug_force_gemm_form(tile_edge=0, ring_slots=0):
 def mom_debug_force_pipeline(on):
     """Testing aid: make mom_mlp_prefill_pipelined always use its two-stream schedule."""
     return lib().mom_debug_force_pipeline(1 if on else 0)
+
+
+def mom_debug_mfma_probe(a, b, iters, workgroups, sink, stream=None):
+    """Measurement aid: register-only MFMA loop on operand fragments taken from bf16 tensors a and b;
+    returns the flop of the launch (time it with events on the stream)."""
+    if sink.numel() < workgroups * 256 or sink.dtype != torch.float32:
+        raise ValueError("sink must hold workgroups*256 float32")
+    rc = lib().mom_debug_mfma_probe(_ptr(a), _nbytes(a), _ptr(b), _nbytes(b), int(iters), int(workgroups),
+                                    _ptr(sink), _stream(stream))
+    if rc != MOM_OK:
+        raise MomError(rc, "mom_debug_mfma_probe")
+    return float(workgroups) * 4 * int(iters) * 64 * 16384
 
 
 def mom_kv_offload(k, v, pinned_host, stream, producer_stream=None, order_event=None, done_event=None,

@@ -14,6 +14,7 @@
 #include "mom_gemm.hip.inc"
 #include "mom_gemm4.hip.inc"
 #include "mom_gemv.hip.inc"
+#include "mom_probe.hip.inc"
 
 // Workspace of mom_mlp_prefill_static: one copy per device, held from the moment the library is
 // loaded on a device until the process ends.  In host code this name is only a handle for
@@ -297,6 +298,20 @@ int mom_debug_force_gemm_form(int tile_edge, int ring_slots) {
     g_force_slots.store(ring_slots, std::memory_order_relaxed);
     g_force_edge.store(tile_edge, std::memory_order_relaxed);
     return MOM_OK;
+}
+
+int mom_debug_mfma_probe(const void* a_bf16, size_t a_bytes, const void* b_bf16, size_t b_bytes, int64_t iters,
+                         int workgroups, float* sink, void* stream) {
+    if (!a_bf16 || !b_bf16 || !sink) return MOM_ERR_NULL;
+    if (!aligned16(a_bf16) || !aligned16(b_bf16) || !aligned16(sink)) return MOM_ERR_ALIGN;
+    if (a_bytes < 16 || b_bytes < 16 || a_bytes / 16 > 0x7fffffffu || b_bytes / 16 > 0x7fffffffu || iters < 0 ||
+        workgroups <= 0 || workgroups > (1 << 20))
+        return MOM_ERR_SHAPE;
+    hipLaunchKernelGGL(momk::mfma_probe_kernel, dim3((unsigned)workgroups), dim3(momk::kProbeThreads), 0,
+                       static_cast<hipStream_t>(stream), static_cast<const momk::u32x4*>(a_bf16),
+                       (unsigned)(a_bytes / 16), static_cast<const momk::u32x4*>(b_bf16), (unsigned)(b_bytes / 16),
+                       (long long)iters, sink);
+    return hipGetLastError() == hipSuccess ? MOM_OK : MOM_ERR_HIP;
 }
 
 int mom_debug_force_pipeline(int on) {

@@ -707,6 +707,17 @@ def test_bench_prints_the_contract_json_line():
     for k in ("bound", "achieved", "peak", "unit", "frac", "traffic"):
         assert k in d["roofline"], k
     assert abs(d["roofline"]["frac"] - d["roofline"]["achieved"] / d["roofline"]["peak"]) < 1e-3
-    for k in ("value", "unit", "cores", "kind", "sample"):
+    for k in ("value", "unit", "cores", "kind", "sample", "single_thread_gflops", "parity_in_bench"):
         assert k in d["cpu_baseline"], k
     assert d["cpu_baseline"]["kind"] == "oracle"
+    assert d["cpu_baseline"]["parity_in_bench"]["ok"] is True
+    # side measurements (outside the timed region) travel in the same line
+    assert d["roofline"]["sustained_peak"] > 0 and d["roofline"]["sustained_peak_constant_operands"] > 0
+    assert abs(d["roofline"]["frac_sustained"] - d["roofline"]["achieved"] / d["roofline"]["sustained_peak"]) < 1e-3
+    for k in ("mini_seq_sweep", "peak_memory", "lmhead", "last_token_mlp", "last_token_branch", "kv_offload"):
+        assert k in d["side"], k
+    pm = d["side"]["peak_memory"]
+    assert pm["mini_seq"]["analytic_workspace_bytes"] == 128 * 1024 * 2
+    assert pm["unchunked"]["analytic_workspace_bytes"] == 512 * 1024 * 2
+    assert pm["mini_seq"]["allocator_peak_growth_bytes"] >= pm["mini_seq"]["analytic_workspace_bytes"]
+    assert d["side"]["kv_offload"]["kv_matches"] is True
