@@ -12,7 +12,6 @@
 
 #include "mom.h"
 #include "mom_gemm.hip.inc"
-#include "mom_gemm4.hip.inc"
 #include "mom_gemv.hip.inc"
 #include "mom_probe.hip.inc"
 
@@ -135,57 +134,57 @@ hipError_t launch_gemm(const unsigned short* X, const unsigned short* W0, const 
     };
     const int64_t tiles = set_tiles(momk::kBM);
     if (tiles > (int64_t)0x1fffffff) return hipErrorInvalidValue;      // tile numbers are 32-bit in the kernels
-    // All kernels give identical bits (every output element sees the same MFMA sequence over k), so
-    // the choice is free: the four-wavefront kernel needs whole 64-wide K stages, and its 128-tile
-    // form is used when 256-tiles would leave a quarter or more of the CUs without work.
-    if (K % 64 == 0) {
-        const int cus = compute_units();
-        if (cus <= 0) return hipErrorInvalidDevice;
-        // Tile edge and ring depth.  256-tiles unless they would leave a quarter or more of the CUs
-        // without work; then 128-tiles, or 64-tiles when even those fill less than half of the CUs; the
-        // small tiles get a deeper ring the fewer workgroups a CU has to hide latency with.
-        // mom_debug_force_gemm_form overrides the choice (for tests, which need every form on shapes of
-        // every size).
-        int edge = 256, slots = 0;
-        const int force = g_force_edge.load(std::memory_order_relaxed);
-        if (force) {
-            edge = force;
-            slots = g_force_slots.load(std::memory_order_relaxed);
-        } else if (!never_small && tiles * 4 <= (int64_t)cus * 3) {
-            edge = (set_tiles(128) * 2 <= cus) ? 64 : 128;
-        }
-        const int64_t t = set_tiles(edge);
-        if (t > (int64_t)0x1fffffff) return hipErrorInvalidValue;
-        if (edge == 256) slots = 5;
-        else if (slots == 0) slots = (edge == 128) ? (t <= cus ? 10 : 5) : (t <= cus ? 20 : (t <= 2 * (int64_t)cus ? 10 : 5));
-        const dim3 grid((unsigned)(a.tiles_per_xcd * 8)), block(momk::k4Threads);
-#define MOM_LAUNCH4(E, S) hipLaunchKernelGGL((momk::gemm4_kernel<EPI, E, S>), grid, block, 0, st, a)
-        if (edge == 256 && slots == 5) MOM_LAUNCH4(256, 5);
-        else if (edge == 128 && slots == 5) MOM_LAUNCH4(128, 5);
-        else if (edge == 128 && slots == 10) MOM_LAUNCH4(128, 10);
-        else if (edge == 64 && slots == 5) MOM_LAUNCH4(64, 5);
-        else if (edge == 64 && slots == 10) MOM_LAUNCH4(64, 10);
-        else if (edge == 64 && slots == 20) MOM_LAUNCH4(64, 20);
-        else return hipErrorInvalidValue;
-#undef MOM_LAUNCH4
-        return hipGetLastError();
+    // All forms give identical bits (every output element sees the same MFMA sequence over k), so the
+    // choice is free.  Tile edge and ring depth: 256-tiles unless they would leave a quarter or more of
+    // the CUs without work; then 128-tiles, or 64-tiles when even those fill less than half of the CUs;
+    // the small tiles get a deeper ring the fewer workgroups a CU has to hide latency with.
+    // mom_debug_force_gemm_form overrides the choice (for tests, which need every form on shapes of
+    // every size).
+    const int cus = compute_units();
+    if (cus <= 0) return hipErrorInvalidDevice;
+    int edge = 256, slots = 0;
+    const int force = g_force_edge.load(std::memory_order_relaxed);
+    if (force) {
+        edge = force;
+        slots = g_force_slots.load(std::memory_order_relaxed);
+    } else if (!never_small && tiles * 4 <= (int64_t)cus * 3) {
+        edge = (set_tiles(128) * 2 <= cus) ? 64 : 128;
     }
-    hipLaunchKernelGGL(momk::gemm_kernel<EPI>, dim3((unsigned)(a.tiles_per_xcd * 8)), dim3(momk::kThreads), 0, st,
-                       a);
+    const int64_t t = set_tiles(edge);
+    if (t > (int64_t)0x1fffffff) return hipErrorInvalidValue;
+    if (edge == 256) slots = 5;
+    else if (slots == 0) slots = (edge == 128) ? (t <= cus ? 10 : 5) : (t <= cus ? 20 : (t <= 2 * (int64_t)cus ? 10 : 5));
+    const dim3 grid((unsigned)(a.tiles_per_xcd * 8)), block(momk::k4Threads);
+#define MOM_LAUNCH4(E, S) hipLaunchKernelGGL((momk::gemm4_kernel<EPI, E, S>), grid, block, 0, st, a)
+    if (edge == 256 && slots == 5) MOM_LAUNCH4(256, 5);
+    else if (edge == 128 && slots == 5) MOM_LAUNCH4(128, 5);
+    else if (edge == 128 && slots == 10) MOM_LAUNCH4(128, 10);
+    else if (edge == 64 && slots == 5) MOM_LAUNCH4(64, 5);
+    else if (edge == 64 && slots == 10) MOM_LAUNCH4(64, 10);
+    else if (edge == 64 && slots == 20) MOM_LAUNCH4(64, 20);
+    else return hipErrorInvalidValue;
+#undef MOM_LAUNCH4
     return hipGetLastError();
 }
 
 template <int MODE>
 hipError_t launch_gemv(const unsigned short* x, const unsigned short* Wa, const unsigned short* Wb, void* y,
                        int64_t R, int64_t K, hipStream_t st) {
-    const int rows_per_block = momk::kGemvWaves * (MODE == momk::MODE_GATEUP ? momk::kGemvStreams / 2 : (MODE == momk::MODE_DOWN ? 1 : momk::kGemvStreams));
-    int64_t blocks = (R + rows_per_block - 1) / rows_per_block;
-    // a few resident workgroups per CU, each looping over rows; the LM head, whose every wavefront keeps
-    // four 1 KiB row streams in flight, measured 5 % faster with 2 workgroups per CU than with 8
-    const int64_t max_blocks = (MODE == momk::MODE_LOGITS) ? 256 * 2 : 256 * 8;
-    if (blocks > max_blocks) blocks = max_blocks;
-    hipLaunchKernelGGL(momk::gemv_kernel<MODE>, dim3((unsigned)blocks), dim3(momk::kGemvWaves * 64),
-                       (size_t)K * 2, st, x, Wa, Wb, y, (int)R, (int)K);
+    // Wavefronts per workgroup, batches per prefetch step and resident workgroups per CU, as measured on the
+    // Llama-3-8B shapes (sweep over 2..16 wavefronts, 1..4 batches, 1..16 workgroups per CU):
+    //   LM head  V x 4096     4 wavefronts, 1 batch, 2 per CU   (8 wavefronts per CU, each looping over row groups)
+    //   gate/up  2 x I x 4096 2 wavefronts, 2 batches, 16 per CU
+    //   down     H x 14336    8 wavefronts, 1 batch, 4 per CU   (the workgroup shares one 28 KiB copy of h in LDS)
+    constexpr int WAVES = (MODE == momk::MODE_LOGITS) ? 4 : (MODE == momk::MODE_GATEUP ? 2 : 8);
+    constexpr int U = (MODE == momk::MODE_GATEUP) ? 2 : 1;
+    constexpr int PER_CU = (MODE == momk::MODE_LOGITS) ? 2 : (MODE == momk::MODE_GATEUP ? 16 : 4);
+    const int cus = compute_units();
+    if (cus <= 0) return hipErrorInvalidDevice;
+    const int64_t groups = (R + momk::gemv_rows_per_group(MODE) - 1) / momk::gemv_rows_per_group(MODE);
+    int64_t blocks = (groups + WAVES - 1) / WAVES;
+    if (blocks > (int64_t)cus * PER_CU) blocks = (int64_t)cus * PER_CU;
+    hipLaunchKernelGGL((momk::gemv_kernel<MODE, WAVES, U>), dim3((unsigned)blocks), dim3(WAVES * 64), (size_t)K * 2, st,
+                       x, Wa, Wb, y, (int)R, (int)K);
     return hipGetLastError();
 }
 

@@ -108,7 +108,7 @@ def test_tiny_workload_matches_oracle_and_unchunked():
 
 
 @pytest.mark.parametrize("S,H,I", [(300, 96, 160), (257, 256, 288), (1, 64, 32), (513, 32, 1056), (40, 544, 96),
-                                   # H and I multiples of 64 (the four-wavefront kernel): one stage, ring wrap-around
+                                   # H and I multiples of 64: whole stages only (one stage, ring wrap-around)
                                    (257, 64, 64), (300, 128, 192), (130, 320, 448), (700, 384, 640)])
 def test_ragged_shapes_match_oracle(S, H, I):
     dev = _dev()
@@ -576,7 +576,9 @@ def test_mistral_7b_448k_full_size():
 
 @pytest.mark.parametrize("S,H,I", [(257, 64, 64), (300, 128, 192), (700, 384, 640), (1100, 256, 1024),
                                    # long contractions: 32 / 40 stages, several periods of the 20-slot ring
-                                   (600, 2048, 2560)])
+                                   (600, 2048, 2560),
+                                   # odd multiples of 32: a final half stage (K = 32: nothing but that half stage)
+                                   (300, 96, 160), (130, 32, 32), (513, 32, 1056), (450, 352, 96)])
 def test_gemm_tile_forms_give_identical_bits(S, H, I, gemm_form):
     """The forms of the four-wavefront kernel (tile edge 256 / 128 / 64, LDS ring of 5 / 10 / 20 slots) -
     the library picks one by the number of tiles in a launch; mom_debug_force_gemm_form overrides it -
@@ -624,21 +626,25 @@ def test_every_tile_form_at_production_contraction_lengths(name, gemm_form):
             assert bits_equal(o, base), f"{name}: form {form}, C={C}"
 
 
-def test_eight_wavefront_kernel_at_mid_size_matches_oracle():
-    """Contraction lengths that are odd multiples of 32 run the eight-wavefront kernel (the
-    four-wavefront one needs whole 64-wide stages): a mid-size case with its final half stage in both
-    projections, sampled rows against the oracle, mini-sequence against full sequence bit for bit."""
+def test_final_half_stage_at_mid_size_matches_oracle(gemm_form):
+    """Contraction lengths that are odd multiples of 32 end with a half stage after the stage loop: a
+    mid-size case with that half stage in both projections, sampled rows against the oracle,
+    mini-sequence against full sequence and every tile form against the others bit for bit."""
     dev = _dev()
-    wl = synth.Workload("g8", S=4096 + 300, H=1056, I=2080, mini_seq=1024, seed=31, w_std=0.03)
+    wl = synth.Workload("half", S=4096 + 300, H=1056, I=2080, mini_seq=1024, seed=31, w_std=0.03)
     x, wg, wu, wd = synth.mlp_inputs(wl, device=dev)
     out, _ = run_mlp(x, wg, wu, wd, wl.mini_seq)
     rows = synth.parity_rows(wl.S, wl.mini_seq, n_random=32, seed=wl.seed, residues=256)
     rows_t = torch.from_numpy(rows).to(dev)
     ref = oracle.mlp_rows(synth.bits(x[rows_t]), synth.bits(wg), synth.bits(wu), synth.bits(wd))
-    assert_close_to_oracle(_f32(out[rows_t]), ref, "eight-wavefront kernel, sampled rows")
+    assert_close_to_oracle(_f32(out[rows_t]), ref, "final half stage, sampled rows")
     for C in (0, 300, 2048):
         o, _ = run_mlp(x, wg, wu, wd, C)
         assert bits_equal(o, out), f"C={C}"
+    for form in FORMS:
+        gemm_form(*form)
+        o, _ = run_mlp(x, wg, wu, wd, 700)
+        assert bits_equal(o, out), f"form {form}"
 
 
 def test_entry_points_can_be_captured_in_a_hip_graph():
