@@ -6,6 +6,7 @@ numpy uint16 bit patterns.  Only tests, the smoke check and the benchmark's
 cpu_baseline leg may import this package; the product path never does.
 """
 import ctypes
+import os
 
 import numpy as np
 
@@ -17,7 +18,8 @@ _lib = None
 def _load():
     global _lib
     if _lib is None:
-        lib = ctypes.CDLL(_build.build(force=False))
+        # MOM_ORACLE_SANITIZED=1: the AddressSanitizer / UBSan build (the sanitizer run of the tests)
+        lib = ctypes.CDLL(_build.build(force=False, sanitize=os.environ.get("MOM_ORACLE_SANITIZED") == "1"))
         u16p = ctypes.POINTER(ctypes.c_uint16)
         f32p = ctypes.POINTER(ctypes.c_float)
         i64p = ctypes.POINTER(ctypes.c_int64)
