@@ -273,6 +273,32 @@ def one_token_kernels(binding, synth, torch, tensors, dev, H, I, V):
     both = res["lmhead"]["us"] + res["last_token_mlp"]["us"]
     res["last_token_branch"] = {"us": round(both, 2), "bytes": nbytes + mb,
                                 "frac_hbm_peak": round((nbytes + mb) / (both * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4)}
+    # the whole branch (gate/up GEMV, down GEMV, LM head on the MLP's output) as ONE captured HIP graph
+    try:
+        wlm = synth.lmhead_inputs(lm, device=dev)[1]
+        st = torch.cuda.current_stream()
+
+        def branch():
+            binding.mom_mlp_last(x[-1], wg, wu, wd, o1, wsl)
+            binding.mom_lmhead_last(o1, wlm, logits)
+        side = torch.cuda.Stream()
+        side.wait_stream(st)
+        with torch.cuda.stream(side):
+            branch()
+        st.wait_stream(side)
+        torch.cuda.synchronize()
+        eager = logits.clone()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            branch()
+        torch.cuda.synchronize()
+        logits.zero_()
+        t = event_time(torch, graph.replay, reps=20, warmup=3)
+        res["last_token_branch"]["hip_graph_us"] = round(t * 1e6, 2)
+        res["last_token_branch"]["hip_graph_frac_hbm_peak"] = round((nbytes + mb) / t / 1e9 / HBM_PEAK_GBPS, 4)
+        res["last_token_branch"]["hip_graph_matches_eager"] = bool(torch.equal(eager, logits))
+    except Exception as e:                       # a side measurement must not take the benchmark down
+        res["last_token_branch"]["hip_graph_error"] = repr(e)[:200]
     return res
 
 

@@ -124,8 +124,8 @@ hipError_t launch_gemm(const unsigned short* X, const unsigned short* W0, const 
     a.X = X; a.W0 = W0; a.W1 = W1; a.O = O;
     a.M = M; a.N = N; a.K = K;
     a.group_m = momk::kGroupM;
-    auto set_tiles = [&](int tile) {
-        const int tile_n = (EPI == momk::EPI_GATEUP) ? tile / 2 : tile;
+    auto set_tiles = [&](int tile, int tile_w = 0) {           // tile_w: weight rows per tile of the down projection
+        const int tile_n = (EPI == momk::EPI_GATEUP) ? tile / 2 : (tile_w ? tile_w : tile);
         a.tiles_m = (M + tile - 1) / tile;
         a.tiles_n = (N + tile_n - 1) / tile_n;
         const int64_t tiles = (int64_t)a.tiles_m * a.tiles_n;
@@ -138,25 +138,44 @@ hipError_t launch_gemm(const unsigned short* X, const unsigned short* W0, const 
     // choice is free.  Tile edge and ring depth: 256-tiles unless they would leave a quarter or more of
     // the CUs without work; then 128-tiles, or 64-tiles when even those fill less than half of the CUs;
     // the small tiles get a deeper ring the fewer workgroups a CU has to hide latency with.
+    // Down projection with 256-row tiles: 256, 224 or 192 weight rows per tile, whichever needs the
+    // least time in whole rounds of the CUs (rounds x width; 3584 output columns on 256 CUs with 32
+    // token tiles are 1.75 rounds of 256-wide tiles but exactly 2 rounds of 224-wide ones).
     // mom_debug_force_gemm_form overrides the choice (for tests, which need every form on shapes of
     // every size).
     const int cus = compute_units();
     if (cus <= 0) return hipErrorInvalidDevice;
-    int edge = 256, slots = 0;
+    int edge = 256, slots = 0, width = 256;
     const int force = g_force_edge.load(std::memory_order_relaxed);
     if (force) {
-        edge = force;
+        edge = (force == 224 || force == 192) ? 256 : force;
+        width = (EPI == momk::EPI_DOWN && edge == 256) ? force : edge;
         slots = g_force_slots.load(std::memory_order_relaxed);
     } else if (!never_small && tiles * 4 <= (int64_t)cus * 3) {
         edge = (set_tiles(128) * 2 <= cus) ? 64 : 128;
+        width = edge;
+    } else if (EPI == momk::EPI_DOWN) {
+        int64_t best = 0;
+        for (int w : {256, 224, 192}) {
+            const int64_t cost = ((set_tiles(256, w) + cus - 1) / cus) * w;
+            if (best == 0 || cost < best) { best = cost; width = w; }
+        }
     }
-    const int64_t t = set_tiles(edge);
+    const int64_t t = set_tiles(edge, width);
     if (t > (int64_t)0x1fffffff) return hipErrorInvalidValue;
     if (edge == 256) slots = 5;
     else if (slots == 0) slots = (edge == 128) ? (t <= cus ? 10 : 5) : (t <= cus ? 20 : (t <= 2 * (int64_t)cus ? 10 : 5));
     const dim3 grid((unsigned)(a.tiles_per_xcd * 8)), block(momk::k4Threads);
 #define MOM_LAUNCH4(E, S) hipLaunchKernelGGL((momk::gemm4_kernel<EPI, E, S>), grid, block, 0, st, a)
-    if (edge == 256 && slots == 5) MOM_LAUNCH4(256, 5);
+    if (edge == 256 && slots == 5) {
+        if constexpr (EPI == momk::EPI_DOWN) {
+            if (width == 224) hipLaunchKernelGGL((momk::gemm4_kernel<EPI, 256, 5, 224>), grid, block, 0, st, a);
+            else if (width == 192) hipLaunchKernelGGL((momk::gemm4_kernel<EPI, 256, 5, 192>), grid, block, 0, st, a);
+            else MOM_LAUNCH4(256, 5);
+        } else {
+            MOM_LAUNCH4(256, 5);
+        }
+    }
     else if (edge == 128 && slots == 5) MOM_LAUNCH4(128, 5);
     else if (edge == 128 && slots == 10) MOM_LAUNCH4(128, 10);
     else if (edge == 64 && slots == 5) MOM_LAUNCH4(64, 5);
@@ -290,7 +309,8 @@ int mom_init(void) {
 }
 
 int mom_debug_force_gemm_form(int tile_edge, int ring_slots) {
-    const bool ok = (tile_edge == 0 && ring_slots == 0) || (tile_edge == 256 && (ring_slots == 0 || ring_slots == 5)) ||
+    const bool ok = (tile_edge == 0 && ring_slots == 0) ||
+                    ((tile_edge == 256 || tile_edge == 224 || tile_edge == 192) && (ring_slots == 0 || ring_slots == 5)) ||
                     (tile_edge == 128 && (ring_slots == 0 || ring_slots == 5 || ring_slots == 10)) ||
                     (tile_edge == 64 && (ring_slots == 0 || ring_slots == 5 || ring_slots == 10 || ring_slots == 20));
     if (!ok) return MOM_ERR_SHAPE;

@@ -88,7 +88,8 @@ def gemm_form():
     binding.mom_debug_force_gemm_form(0, 0)
 
 
-FORMS = ((256, 5), (128, 5), (128, 10), (64, 5), (64, 10), (64, 20))
+FORMS = ((256, 5), (128, 5), (128, 10), (64, 5), (64, 10), (64, 20),
+         (224, 5), (192, 5))        # 256 x 224 / 256 x 192 tiles for the down projection
 
 
 # ------------------------------------------------------------------ small shapes, full compare
@@ -591,7 +592,8 @@ def test_gemm_tile_forms_give_identical_bits(S, H, I, gemm_form):
     outs = []
     for form, C in (((256, 0), 0), ((128, 10), 0), ((128, 5), 0), ((64, 5), 0), ((64, 10), 0), ((64, 20), 0),
                     ((256, 5), 256), ((128, 5), 200), ((128, 10), 100), ((64, 20), 96), ((64, 5), 300),
-                    ((64, 10), 130), ((128, 0), 0), ((64, 0), 0), ((0, 0), 0)):
+                    ((64, 10), 130), ((128, 0), 0), ((64, 0), 0), ((224, 0), 0), ((192, 5), 0), ((224, 5), 300),
+                    ((192, 0), 77), ((0, 0), 0)):
         gemm_form(*form)
         outs.append(run_mlp(xd, wgd, wud, wdd, C)[0])
     for i, o in enumerate(outs[1:]):
