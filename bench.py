@@ -25,9 +25,11 @@ if ROOT not in sys.path:
 BF16_MFMA_PEAK_TFLOPS = 2500.0      # MI355X dense bf16 matrix peak (published figure)
 HBM_PEAK_GBPS = 8000.0
 # Bytes between the L2s and the memory fabric per launch of the gate/up kernel (rocprofv3 FETCH_SIZE + WRITE_SIZE,
-# each scaled by what the same counter reads for a 1 GiB copy kernel; the summaries are under profiles/).
-# Not measured live: the figure does not depend on the machine's clock.
-GATEUP_TRAFFIC_BYTES = {("llama3_8b_32k", 4096): 1.527e9}
+# each scaled by what the same counter reads for a 1 GiB copy kernel: x 2.000 and x 1.000; the summary with the
+# commands is profiles/gemm_kernels_llama3_8b_32k_counters.txt).  Not measured live: the figure is a property of
+# the tiling (every operand panel once per block of 32 resident tiles per L2), not of the machine's clock.
+GATEUP_TRAFFIC_BYTES = {("llama3_8b_32k", 4096): 1.527e9, ("llama3_8b_128k", 8192): 3.054e9,
+                        ("qwen25_7b_256k", 8192): 3.599e9, ("mistral_7b_448k", 16384): 6.108e9}
 
 
 def parse():
