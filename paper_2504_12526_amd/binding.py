@@ -69,7 +69,7 @@ def lib():
         L.mom_init.restype = ctypes.c_int
         L.mom_init.argtypes = []
         L.mom_debug_force_gemm_form.restype = ctypes.c_int
-        L.mom_debug_force_gemm_form.argtypes = [ctypes.c_int, ctypes.c_int]
+        L.mom_debug_force_gemm_form.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int]
         L.mom_debug_mfma_probe.restype = ctypes.c_int
         L.mom_debug_mfma_probe.argtypes = [vp, sz, vp, sz, i64, ctypes.c_int, vp, vp]
         L.mom_debug_force_pipeline.restype = ctypes.c_int
@@ -172,9 +172,9 @@ def mom_init():
     return rc
 
 
-def mom_debug_force_gemm_form(tile_edge=0, ring_slots=0):
-    """Testing aid: force the tile form of the matrix-core kernels; (0, 0) = the library's choice."""
-    rc = lib().mom_debug_force_gemm_form(int(tile_edge), int(ring_slots))
+def mom_debug_force_gemm_form(tile_edge=0, ring_slots=0, down_width=0):
+    """Testing aid: force the tile form of the matrix-core kernels; (0, 0, 0) = the library's choice."""
+    rc = lib().mom_debug_force_gemm_form(int(tile_edge), int(ring_slots), int(down_width))
     if rc != MOM_OK:
         raise MomError(rc, "mom_debug_force_gemm_form")
     return rc

@@ -65,7 +65,7 @@ struct DeviceInfo {
 DeviceInfo g_dev[kMaxDevices];
 
 // Testing overrides (mom_debug_force_gemm_form / mom_debug_force_pipeline); 0 = the library chooses.
-std::atomic<int> g_force_edge{0}, g_force_slots{0}, g_force_pipeline{0};
+std::atomic<int> g_force_edge{0}, g_force_slots{0}, g_force_width{0}, g_force_pipeline{0};
 
 DeviceInfo* current_device_info() {
     int dev = 0;
@@ -138,9 +138,11 @@ hipError_t launch_gemm(const unsigned short* X, const unsigned short* W0, const 
     // choice is free.  Tile edge and ring depth: 256-tiles unless they would leave a quarter or more of
     // the CUs without work; then 128-tiles, or 64-tiles when even those fill less than half of the CUs;
     // the small tiles get a deeper ring the fewer workgroups a CU has to hide latency with.
-    // Down projection with 256-row tiles: 256, 224 or 192 weight rows per tile, whichever needs the
-    // least time in whole rounds of the CUs (rounds x width; 3584 output columns on 256 CUs with 32
-    // token tiles are 1.75 rounds of 256-wide tiles but exactly 2 rounds of 224-wide ones).
+    // Down projection with 256-row tiles: 256, 224, 192, 160 or 128 weight rows per tile, whichever needs
+    // the least time in whole rounds of the CUs (rounds x width, a narrower tile charged a little more per
+    // column for the token fragments it shares among fewer MFMAs): 3584 output columns with 32 token tiles
+    // are 1.75 rounds of 256-wide tiles on 256 CUs but exactly 2 rounds of 224-wide ones, and the 128
+    // full-size tiles of a 2048-row mini-sequence at 4096 columns are one round of 256 tiles 128 wide.
     // mom_debug_force_gemm_form overrides the choice (for tests, which need every form on shapes of
     // every size).
     const int cus = compute_units();
@@ -148,17 +150,27 @@ hipError_t launch_gemm(const unsigned short* X, const unsigned short* W0, const 
     int edge = 256, slots = 0, width = 256;
     const int force = g_force_edge.load(std::memory_order_relaxed);
     if (force) {
-        edge = (force == 224 || force == 192) ? 256 : force;
-        width = (EPI == momk::EPI_DOWN && edge == 256) ? force : edge;
-        slots = g_force_slots.load(std::memory_order_relaxed);
-    } else if (!never_small && tiles * 4 <= (int64_t)cus * 3) {
-        edge = (set_tiles(128) * 2 <= cus) ? 64 : 128;
+        edge = force;
         width = edge;
-    } else if (EPI == momk::EPI_DOWN) {
+        const int fw = g_force_width.load(std::memory_order_relaxed);
+        if (EPI == momk::EPI_DOWN && edge == 256 && fw) width = fw;
+        slots = g_force_slots.load(std::memory_order_relaxed);
+    } else {
+        // time in units of 1/1000 of a 256 x 256 tile: rounds x width x (1 + what the narrower tile costs per column)
+        auto down_cost = [&](int w) {
+            static const int per_mille[5] = {1000, 1010, 1030, 1060, 1100};     // 256, 224, 192, 160, 128
+            return ((set_tiles(256, w) + cus - 1) / cus) * w * per_mille[(256 - w) / 32];
+        };
         int64_t best = 0;
-        for (int w : {256, 224, 192}) {
-            const int64_t cost = ((set_tiles(256, w) + cus - 1) / cus) * w;
-            if (best == 0 || cost < best) { best = cost; width = w; }
+        if (EPI == momk::EPI_DOWN)
+            for (int w : {256, 224, 192, 160, 128}) {
+                const int64_t cost = down_cost(w);
+                if (best == 0 || cost < best) { best = cost; width = w; }
+            }
+        const int64_t t256 = set_tiles(256, width);
+        if (!never_small && t256 * 4 <= (int64_t)cus * 3) {     // even so a quarter or more of the CUs without work
+            edge = (set_tiles(128) * 2 <= cus) ? 64 : 128;
+            width = edge;
         }
     }
     const int64_t t = set_tiles(edge, width);
@@ -171,6 +183,8 @@ hipError_t launch_gemm(const unsigned short* X, const unsigned short* W0, const 
         if constexpr (EPI == momk::EPI_DOWN) {
             if (width == 224) hipLaunchKernelGGL((momk::gemm4_kernel<EPI, 256, 5, 224>), grid, block, 0, st, a);
             else if (width == 192) hipLaunchKernelGGL((momk::gemm4_kernel<EPI, 256, 5, 192>), grid, block, 0, st, a);
+            else if (width == 160) hipLaunchKernelGGL((momk::gemm4_kernel<EPI, 256, 5, 160>), grid, block, 0, st, a);
+            else if (width == 128) hipLaunchKernelGGL((momk::gemm4_kernel<EPI, 256, 5, 128>), grid, block, 0, st, a);
             else MOM_LAUNCH4(256, 5);
         } else {
             MOM_LAUNCH4(256, 5);
@@ -308,12 +322,15 @@ int mom_init(void) {
     return MOM_OK;
 }
 
-int mom_debug_force_gemm_form(int tile_edge, int ring_slots) {
-    const bool ok = (tile_edge == 0 && ring_slots == 0) ||
-                    ((tile_edge == 256 || tile_edge == 224 || tile_edge == 192) && (ring_slots == 0 || ring_slots == 5)) ||
+int mom_debug_force_gemm_form(int tile_edge, int ring_slots, int down_width) {
+    const bool wok = down_width == 0 || (tile_edge == 256 && (down_width == 256 || down_width == 224 || down_width == 192 ||
+                                                              down_width == 160 || down_width == 128));
+    const bool ok = wok && ((tile_edge == 0 && ring_slots == 0) ||
+                    (tile_edge == 256 && (ring_slots == 0 || ring_slots == 5)) ||
                     (tile_edge == 128 && (ring_slots == 0 || ring_slots == 5 || ring_slots == 10)) ||
-                    (tile_edge == 64 && (ring_slots == 0 || ring_slots == 5 || ring_slots == 10 || ring_slots == 20));
+                    (tile_edge == 64 && (ring_slots == 0 || ring_slots == 5 || ring_slots == 10 || ring_slots == 20)));
     if (!ok) return MOM_ERR_SHAPE;
+    g_force_width.store(down_width, std::memory_order_relaxed);
     g_force_slots.store(ring_slots, std::memory_order_relaxed);
     g_force_edge.store(tile_edge, std::memory_order_relaxed);
     return MOM_OK;

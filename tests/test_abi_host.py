@@ -119,10 +119,12 @@ def test_lmhead_and_offload_argument_validation():
 
 def test_debug_overrides_validate_their_arguments():
     L = binding.lib()
-    for ok in ((256, 0), (256, 5), (128, 5), (128, 10), (64, 5), (64, 10), (64, 20), (128, 0), (64, 0), (224, 0),
-               (224, 5), (192, 5), (0, 0)):
+    for ok in ((256, 0, 0), (256, 5, 0), (128, 5, 0), (128, 10, 0), (64, 5, 0), (64, 10, 0), (64, 20, 0), (128, 0, 0),
+               (64, 0, 0), (256, 0, 224), (256, 5, 224), (256, 5, 192), (256, 5, 160), (256, 5, 128), (256, 5, 256),
+               (0, 0, 0)):
         assert L.mom_debug_force_gemm_form(*ok) == binding.MOM_OK
-    for bad in ((100, 0), (256, 10), (128, 20), (64, 3), (0, 5), (-64, 0), (224, 10), (160, 0)):
+    for bad in ((100, 0, 0), (256, 10, 0), (128, 20, 0), (64, 3, 0), (0, 5, 0), (-64, 0, 0), (224, 5, 0), (128, 5, 128),
+                (256, 5, 96), (0, 0, 224)):
         assert L.mom_debug_force_gemm_form(*bad) == binding.MOM_ERR_SHAPE
     assert L.mom_debug_force_pipeline(1) == binding.MOM_OK and L.mom_debug_force_pipeline(0) == binding.MOM_OK
 

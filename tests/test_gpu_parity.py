@@ -85,11 +85,12 @@ def gemm_form():
     """Callable (edge, slots) that forces a tile form of the matrix-core kernels; the library's own
     choice is restored afterwards."""
     yield binding.mom_debug_force_gemm_form
-    binding.mom_debug_force_gemm_form(0, 0)
+    binding.mom_debug_force_gemm_form(0, 0, 0)
 
 
 FORMS = ((256, 5), (128, 5), (128, 10), (64, 5), (64, 10), (64, 20),
-         (224, 5), (192, 5))        # 256 x 224 / 256 x 192 tiles for the down projection
+         # 256-row tiles with 224 ... 128 weight rows for the down projection
+         (256, 5, 224), (256, 5, 192), (256, 5, 160), (256, 5, 128))
 
 
 # ------------------------------------------------------------------ small shapes, full compare
@@ -592,8 +593,9 @@ def test_gemm_tile_forms_give_identical_bits(S, H, I, gemm_form):
     outs = []
     for form, C in (((256, 0), 0), ((128, 10), 0), ((128, 5), 0), ((64, 5), 0), ((64, 10), 0), ((64, 20), 0),
                     ((256, 5), 256), ((128, 5), 200), ((128, 10), 100), ((64, 20), 96), ((64, 5), 300),
-                    ((64, 10), 130), ((128, 0), 0), ((64, 0), 0), ((224, 0), 0), ((192, 5), 0), ((224, 5), 300),
-                    ((192, 0), 77), ((0, 0), 0)):
+                    ((64, 10), 130), ((128, 0), 0), ((64, 0), 0), ((256, 0, 224), 0), ((256, 5, 192), 0),
+                    ((256, 5, 224), 300), ((256, 0, 192), 77), ((256, 5, 160), 0), ((256, 5, 128), 0),
+                    ((256, 0, 160), 200), ((256, 0, 128), 513), ((0, 0), 0)):
         gemm_form(*form)
         outs.append(run_mlp(xd, wgd, wud, wdd, C)[0])
     for i, o in enumerate(outs[1:]):
@@ -602,7 +604,8 @@ def test_gemm_tile_forms_give_identical_bits(S, H, I, gemm_form):
 
 
 def test_forced_form_validation(gemm_form):
-    for bad in ((100, 0), (256, 10), (128, 20), (64, 3), (0, 5), (-64, 0)):
+    for bad in ((100, 0, 0), (256, 10, 0), (128, 20, 0), (64, 3, 0), (0, 5, 0), (-64, 0, 0), (128, 5, 128), (256, 5, 96),
+                (0, 0, 224)):
         assert binding.lib().mom_debug_force_gemm_form(*bad) == binding.MOM_ERR_SHAPE
 
 
