@@ -158,7 +158,7 @@ hipError_t launch_gemm(const unsigned short* X, const unsigned short* W0, const 
     } else {
         // time in units of 1/1000 of a 256 x 256 tile: rounds x width x (1 + what the narrower tile costs per column)
         auto down_cost = [&](int w) {
-            static const int per_mille[5] = {1000, 1010, 1030, 1060, 1100};     // 256, 224, 192, 160, 128
+            static const int per_mille[5] = {1000, 1030, 1030, 1050, 1240};     // 256, 224, 192, 160, 128 (measured)
             return ((set_tiles(256, w) + cus - 1) / cus) * w * per_mille[(256 - w) / 32];
         };
         int64_t best = 0;
