@@ -435,7 +435,7 @@ def main():
         "pct_bf16_mfma_peak": round(100.0 * tflops / BF16_MFMA_PEAK_TFLOPS, 2),
         "workspace_bytes": ws_bytes, "unchunked_workspace_bytes": S * I * 2,
         "device": device_info(torch, dev),
-        "roofline": {"bound": "mfma", "kernel": ("gemm4_kernel<EPI_GATEUP>" if H % 64 == 0 else "gemm_kernel<EPI_GATEUP>") + " (gate/up GEMM + SiLU*up epilogue)",
+        "roofline": {"bound": "mfma", "kernel": "gemm4_kernel<EPI_GATEUP, ...> (gate/up GEMM + SiLU*up epilogue)",
                      "achieved": round(gu_tflops, 2), "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(gu_tflops / BF16_MFMA_PEAK_TFLOPS, 4),
                      "traffic": GATEUP_TRAFFIC_BYTES.get((wl.name, C)),

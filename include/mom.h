@@ -12,8 +12,8 @@
  *     Results are valid once the caller has synchronised the stream (or the
  *     event the call records).
  *   - The library allocates nothing.  The only state it keeps is what it looks up once per
- *     device (compute-unit count, address of the static workspace of mom_mlp_prefill_static)
- *     and the two testing overrides at the end of this header.
+ *     device (compute-unit count, address of the static workspace of
+ *     mom_mlp_prefill_static) and the testing overrides at the end of this header.
  *   - Return value: a `mom_status`; 0 is success.  Arguments are validated
  *     before anything is enqueued, so a non-zero status other than
  *     MOM_ERR_HIP means nothing was launched.
@@ -50,8 +50,9 @@ const char *mom_status_string(int status);
 /*
  * Optional set-up for the current HIP device: looks up what the other calls otherwise look up
  * on their first use on a device (the compute-unit count, the device address of the static
- * workspace of mom_mlp_prefill_static), so that those calls make no runtime query afterwards.  Call it once per device, with that device current, e.g. before
- * a stream capture.  Returns MOM_ERR_HIP when there is no usable device.
+ * workspace of mom_mlp_prefill_static), so that those calls make no runtime query afterwards.
+ * Call it once per device, with that device current, e.g. before a stream capture.  Returns
+ * MOM_ERR_HIP when there is no usable device.
  */
 int mom_init(void);
 

@@ -162,7 +162,7 @@ hipError_t launch_gemm(const unsigned short* X, const unsigned short* W0, const 
             return ((set_tiles(256, w) + cus - 1) / cus) * w * per_mille[(256 - w) / 32];
         };
         int64_t best = 0;
-        if (EPI == momk::EPI_DOWN)
+        if (EPI == momk::EPI_DOWN && !never_small)       // (beside a chip-filling gate/up kernel: full-size tiles, however few)
             for (int w : {256, 224, 192, 160, 128}) {
                 const int64_t cost = down_cost(w);
                 if (best == 0 || cost < best) { best = cost; width = w; }
