@@ -109,6 +109,35 @@ def test_tiny_workload_matches_oracle_and_unchunked():
     assert bits_equal(out, full)
 
 
+def _assert_within_one_bf16_ulp(out, ref_rounded_h, what):
+    """Tighter than the stated bar (a diagnostic of the rounding contract): against the oracle evaluated with
+    the intermediate rounded once to bf16 as the GPU's workspace is, the bf16 output may differ from the
+    rounded reference by one unit in the last place at most (summation order), and mostly not at all."""
+    ref_bf16 = torch.from_numpy(ref_rounded_h).to(torch.bfloat16).to(torch.float32).numpy()
+    got = _f32(out)
+    ulp = np.maximum(np.abs(ref_rounded_h), 1e-30) * 2.0 ** -7          # spacing of bf16 at |ref| is 2^-8..2^-7 relative
+    rms = np.sqrt(np.mean(ref_rounded_h.astype(np.float64) ** 2))
+    bad = np.abs(got - ref_bf16) > ulp + 2.0 ** -9 * rms                # near zero: absolute, relative to the tensor's scale
+    assert not bad.any(), f"{what}: {int(bad.sum())} elements more than one bf16 ulp off"
+    same = float(np.mean(got == ref_bf16))
+    assert same >= 0.9, f"{what}: only {same:.3f} of the elements equal the rounded reference"
+
+
+def test_rounding_contract_against_the_oracle_with_rounded_intermediate():
+    dev = _dev()
+    for wl in (synth.WORKLOADS["tiny"], synth.Workload("r2", S=300, H=1056, I=2080, mini_seq=128, seed=8, w_std=0.03)):
+        x, wg, wu, wd = synth.mlp_inputs(wl)
+        ref = oracle.mlp_rows(*(synth.bits(t) for t in (x, wg, wu, wd)), round_h=True)
+        out, _ = run_mlp(*(t.to(dev) for t in (x, wg, wu, wd)), wl.mini_seq)
+        _assert_within_one_bf16_ulp(out, ref, wl.name)
+        # the one-token path on the last row follows the same contract
+        last = torch.empty((wl.H,), dtype=torch.bfloat16, device=dev)
+        ws = torch.empty(wl.I * 2, dtype=torch.uint8, device=dev)
+        binding.mom_mlp_last(x[-1].to(dev), wg.to(dev), wu.to(dev), wd.to(dev), last, ws)
+        torch.cuda.synchronize()
+        _assert_within_one_bf16_ulp(last, ref[-1], wl.name + " last token")
+
+
 @pytest.mark.parametrize("S,H,I", [(300, 96, 160), (257, 256, 288), (1, 64, 32), (513, 32, 1056), (40, 544, 96),
                                    # H and I multiples of 64: whole stages only (one stage, ring wrap-around)
                                    (257, 64, 64), (300, 128, 192), (130, 320, 448), (700, 384, 640)])
@@ -504,6 +533,8 @@ def _full_size_case(name, sweep=(), check_unchunked=True):
     rows_t = torch.from_numpy(rows).to(dev)
     ref = oracle.mlp_rows(synth.bits(x[rows_t]), synth.bits(wg), synth.bits(wu), synth.bits(wd))
     assert_close_to_oracle(_f32(out[rows_t]), ref, f"{name} sampled rows")
+    ref_r = oracle.mlp_rows(synth.bits(x[rows_t[:64]]), synth.bits(wg), synth.bits(wu), synth.bits(wd), round_h=True)
+    _assert_within_one_bf16_ulp(out[rows_t[:64]], ref_r, f"{name} sampled rows, rounded intermediate")
     if check_unchunked:
         full, nfull = run_mlp(x, wg, wu, wd, 0)
         assert nfull == wl.S * wl.I * 2
