@@ -266,6 +266,44 @@ def test_library_allocates_nothing():
     assert free1 == free0 and torch.cuda.max_memory_allocated() == peak0
 
 
+def test_two_host_threads_on_two_streams_give_the_sequential_bits():
+    """The entry points keep no per-call state in the library: two host threads, each with its own
+    stream, workspace and output, may call at the same time."""
+    import threading
+    dev = _dev()
+    cases = [synth.Workload("t0", S=1500, H=256, I=1024, mini_seq=512, seed=21),
+             synth.Workload("t1", S=900, H=384, I=640, mini_seq=256, seed=22)]
+    data, want = [], []
+    for wl in cases:
+        t = tuple(v.to(dev) for v in synth.mlp_inputs(wl))
+        data.append(t)
+        want.append(run_mlp(*t, wl.mini_seq)[0])
+    outs = [torch.empty_like(d[0]) for d in data]
+    wss = [torch.empty(binding.mom_mlp_workspace_bytes(wl.S, wl.H, wl.I, wl.mini_seq), dtype=torch.uint8, device=dev)
+           for wl in cases]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    torch.cuda.synchronize()
+    errors = []
+
+    def worker(i):
+        try:
+            for _ in range(20):
+                binding.mom_mlp_prefill(*data[i], cases[i].mini_seq, outs[i], wss[i], stream=streams[i])
+            streams[i].synchronize()
+        except Exception as e:          # noqa: BLE001 - reported below, in the main thread
+            errors.append(e)
+
+    threads = [threading.Thread(target=worker, args=(i,)) for i in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+    torch.cuda.synchronize()
+    for i in range(2):
+        assert bits_equal(outs[i], want[i]), f"thread {i}"
+
+
 # ------------------------------------------------------------------ LM head and last-token branch
 
 @pytest.mark.parametrize("V,H", [(4096, 256), (1001, 4096), (3, 32), (16, 3584), (5000, 416),
