@@ -218,15 +218,17 @@ int mom_kv_reload(const void *pinned_host, void *k, void *v, void *stream, size_
  *
  * mom_debug_force_gemm_form: every later matrix-core launch uses tiles of tile_edge x tile_edge
  * (256, 128 or 64) and an LDS ring of ring_slots slots (256: 5; 128: 5 or 10; 64: 5, 10 or 20;
- * 0 = the library's choice for that edge) whatever the launch's size.  down_width (only with
- * tile_edge 256; 0 = 256) makes the tiles of the down projection 256 token rows x down_width
- * weight rows: 256, 224, 192, 160 or 128.  (0, 0, 0) gives the choice back to the library.
+ * 0 = the library's choice for that edge) whatever the launch's size.  tile_width (only with
+ * tile_edge 256; 0 = 256) is the number of weight rows a tile stages: 256, 224, 192, 160 or 128
+ * make the tiles of the down projection 256 token rows x tile_width output columns; 192 also makes
+ * the gate/up tiles 256 token rows x 96 output columns (96 rows of W_gate and 96 of W_up) instead
+ * of 128.  (0, 0, 0) gives the choice back to the library.
  * All forms give identical bits.  Other values: MOM_ERR_SHAPE, nothing changes.
  *
  * mom_debug_force_pipeline: on != 0 makes mom_mlp_prefill_pipelined use its two-stream schedule
  * whenever there is more than one mini-sequence, also where it was measured not to pay.
  */
-int mom_debug_force_gemm_form(int tile_edge, int ring_slots, int down_width);
+int mom_debug_force_gemm_form(int tile_edge, int ring_slots, int tile_width);
 int mom_debug_force_pipeline(int on);
 
 /*

@@ -172,9 +172,9 @@ def mom_init():
     return rc
 
 
-def mom_debug_force_gemm_form(tile_edge=0, ring_slots=0, down_width=0):
+def mom_debug_force_gemm_form(tile_edge=0, ring_slots=0, tile_width=0):
     """Testing aid: force the tile form of the matrix-core kernels; (0, 0, 0) = the library's choice."""
-    rc = lib().mom_debug_force_gemm_form(int(tile_edge), int(ring_slots), int(down_width))
+    rc = lib().mom_debug_force_gemm_form(int(tile_edge), int(ring_slots), int(tile_width))
     if rc != MOM_OK:
         raise MomError(rc, "mom_debug_force_gemm_form")
     return rc

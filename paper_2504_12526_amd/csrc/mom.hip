@@ -64,6 +64,12 @@ struct DeviceInfo {
 };
 DeviceInfo g_dev[kMaxDevices];
 
+// Gate/up tiles of 96 columns beside those of 128: a column costs the same in either (measured: a round of
+// 256 x 96 tiles takes 0.747 of the time of a round of 256 x 128 tiles), but a last round that fills
+// only part of the CUs is not as dear as a whole one either - the chip is power-limited and clocks the
+// busy CUs higher - so the mix has to save this much of the time in whole rounds before it is used.
+constexpr int kGateUpMixMinGainPerMille = 15;
+
 // Testing overrides (mom_debug_force_gemm_form / mom_debug_force_pipeline); 0 = the library chooses.
 std::atomic<int> g_force_edge{0}, g_force_slots{0}, g_force_width{0}, g_force_pipeline{0};
 
@@ -117,23 +123,60 @@ int check_pinned_host(const void* p, size_t n) {
     return MOM_OK;
 }
 
+// The tile grid of `a` (M, N set) for tiles of `edge` token rows staging `width` weight rows; false if it
+// is empty or too large (tile numbers are 32-bit in the kernels).
+template <int EPI>
+bool set_tile_grid(momk::GemmArgs& a, int edge, int width) {
+    const int tile_n = (EPI == momk::EPI_GATEUP) ? width / 2 : width;
+    a.group_m = momk::kGroupM;
+    a.tiles_m = (a.M + edge - 1) / edge;
+    a.tiles_n = (a.N + tile_n - 1) / tile_n;
+    const int64_t t = (int64_t)a.tiles_m * a.tiles_n;
+    if (t <= 0 || t > (int64_t)0x1fffffff) return false;
+    a.tiles_per_xcd = (int)((t + 7) / 8);
+    return true;
+}
+
+// One launch of gemm4_kernel<EPI, edge, slots, width> over the operands in `a` (M, N, K, ldo set).
+template <int EPI>
+hipError_t launch_gemm_form(momk::GemmArgs a, int edge, int slots, int width, hipStream_t st) {
+    if (!set_tile_grid<EPI>(a, edge, width)) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)(a.tiles_per_xcd * 8)), block(momk::k4Threads);
+#define MOM_LAUNCH4(E, S, W) hipLaunchKernelGGL((momk::gemm4_kernel<EPI, E, S, W>), grid, block, 0, st, a)
+    if (edge == 256 && slots == 5) {
+        if constexpr (EPI == momk::EPI_DOWN) {
+            if (width == 256) MOM_LAUNCH4(256, 5, 256);
+            else if (width == 224) MOM_LAUNCH4(256, 5, 224);
+            else if (width == 192) MOM_LAUNCH4(256, 5, 192);
+            else if (width == 160) MOM_LAUNCH4(256, 5, 160);
+            else if (width == 128) MOM_LAUNCH4(256, 5, 128);
+            else return hipErrorInvalidValue;
+        } else {
+            if (width == 256) MOM_LAUNCH4(256, 5, 256);
+            else if (width == 192) MOM_LAUNCH4(256, 5, 192);
+            else return hipErrorInvalidValue;
+        }
+    }
+    else if (edge == 128 && slots == 5 && width == 128) MOM_LAUNCH4(128, 5, 128);
+    else if (edge == 128 && slots == 10 && width == 128) MOM_LAUNCH4(128, 10, 128);
+    else if (edge == 64 && slots == 5 && width == 64) MOM_LAUNCH4(64, 5, 64);
+    else if (edge == 64 && slots == 10 && width == 64) MOM_LAUNCH4(64, 10, 64);
+    else if (edge == 64 && slots == 20 && width == 64) MOM_LAUNCH4(64, 20, 64);
+    else return hipErrorInvalidValue;
+#undef MOM_LAUNCH4
+    return hipGetLastError();
+}
+
 template <int EPI>
 hipError_t launch_gemm(const unsigned short* X, const unsigned short* W0, const unsigned short* W1,
                        unsigned short* O, int M, int N, int K, hipStream_t st, bool never_small = false) {
     momk::GemmArgs a;
     a.X = X; a.W0 = W0; a.W1 = W1; a.O = O;
-    a.M = M; a.N = N; a.K = K;
-    a.group_m = momk::kGroupM;
-    auto set_tiles = [&](int tile, int tile_w = 0) {           // tile_w: weight rows per tile of the down projection
-        const int tile_n = (EPI == momk::EPI_GATEUP) ? tile / 2 : (tile_w ? tile_w : tile);
-        a.tiles_m = (M + tile - 1) / tile;
-        a.tiles_n = (N + tile_n - 1) / tile_n;
-        const int64_t tiles = (int64_t)a.tiles_m * a.tiles_n;
-        a.tiles_per_xcd = (int)((tiles + 7) / 8);
-        return tiles;
-    };
-    const int64_t tiles = set_tiles(momk::kBM);
-    if (tiles > (int64_t)0x1fffffff) return hipErrorInvalidValue;      // tile numbers are 32-bit in the kernels
+    a.M = M; a.N = N; a.K = K; a.ldo = N;
+    // tiles of a launch with `tile` token rows and `cols` output columns per tile
+    auto tiles_of = [&](int tile, int cols) { return (int64_t)((M + tile - 1) / tile) * ((N + cols - 1) / cols); };
+    const int gu = (EPI == momk::EPI_GATEUP) ? 2 : 1;        // weight rows staged per output column
+    if (tiles_of(momk::kBM, momk::kBW / gu) > (int64_t)0x1fffffff) return hipErrorInvalidValue;
     // All forms give identical bits (every output element sees the same MFMA sequence over k), so the
     // choice is free.  Tile edge and ring depth: 256-tiles unless they would leave a quarter or more of
     // the CUs without work; then 128-tiles, or 64-tiles when even those fill less than half of the CUs;
@@ -143,23 +186,28 @@ hipError_t launch_gemm(const unsigned short* X, const unsigned short* W0, const 
     // column for the token fragments it shares among fewer MFMAs): 3584 output columns with 32 token tiles
     // are 1.75 rounds of 256-wide tiles on 256 CUs but exactly 2 rounds of 224-wide ones, and the 128
     // full-size tiles of a 2048-row mini-sequence at 4096 columns are one round of 256 tiles 128 wide.
+    // Gate/up with 256-row tiles: the first columns in tiles of 128 columns, the rest in tiles of 96, in one
+    // launch of the two-width kernel, where that saves time in whole rounds: 14336 columns with 4 token
+    // tiles are 448 tiles = 1.75 rounds -> 2, but 64 x 128 + 64 x 96 columns are one round of each width
+    // = 1.75 rounds' time.
     // mom_debug_force_gemm_form overrides the choice (for tests, which need every form on shapes of
     // every size).
     const int cus = compute_units();
     if (cus <= 0) return hipErrorInvalidDevice;
     int edge = 256, slots = 0, width = 256;
+    int64_t narrow_tiles_n = 0;          // gate/up: column tiles of the narrow width behind the wide ones
     const int force = g_force_edge.load(std::memory_order_relaxed);
     if (force) {
         edge = force;
         width = edge;
         const int fw = g_force_width.load(std::memory_order_relaxed);
-        if (EPI == momk::EPI_DOWN && edge == 256 && fw) width = fw;
+        if (edge == 256 && fw && (EPI == momk::EPI_DOWN || fw == 192)) width = fw;
         slots = g_force_slots.load(std::memory_order_relaxed);
     } else {
         // time in units of 1/1000 of a 256 x 256 tile: rounds x width x (1 + what the narrower tile costs per column)
         auto down_cost = [&](int w) {
             static const int per_mille[5] = {1000, 1030, 1030, 1050, 1240};     // 256, 224, 192, 160, 128 (measured)
-            return ((set_tiles(256, w) + cus - 1) / cus) * w * per_mille[(256 - w) / 32];
+            return ((tiles_of(256, w) + cus - 1) / cus) * w * per_mille[(256 - w) / 32];
         };
         int64_t best = 0;
         if (EPI == momk::EPI_DOWN && !never_small)       // (beside a chip-filling gate/up kernel: full-size tiles, however few)
@@ -167,37 +215,53 @@ hipError_t launch_gemm(const unsigned short* X, const unsigned short* W0, const 
                 const int64_t cost = down_cost(w);
                 if (best == 0 || cost < best) { best = cost; width = w; }
             }
-        const int64_t t256 = set_tiles(256, width);
+        const int64_t t256 = tiles_of(256, width / gu);
         if (!never_small && t256 * 4 <= (int64_t)cus * 3) {     // even so a quarter or more of the CUs without work
-            edge = (set_tiles(128) * 2 <= cus) ? 64 : 128;
+            edge = (tiles_of(128, 128 / gu) * 2 <= cus) ? 64 : 128;
             width = edge;
+        } else if (EPI == momk::EPI_GATEUP) {
+            // b column tiles of 96 behind a of 128: a = ceil((N - 96 b) / 128); time = rounds x columns per tile
+            const int64_t tm = (M + 255) / 256;
+            auto cost = [&](int64_t b) {
+                const int64_t rest = (int64_t)N - 96 * b;
+                const int64_t wide = rest > 0 ? (rest + 127) / 128 : 0;
+                return ((tm * wide + cus - 1) / cus) * 128 + ((tm * b + cus - 1) / cus) * 96;
+            };
+            const int64_t plain = cost(0);
+            int64_t best_cost = plain;
+            for (int64_t b = 1; b <= ((int64_t)N + 95) / 96; ++b) {
+                const int64_t c = cost(b);
+                if (c < best_cost && c * 1000 <= plain * (1000 - kGateUpMixMinGainPerMille)) { best_cost = c; narrow_tiles_n = b; }
+            }
         }
     }
-    const int64_t t = set_tiles(edge, width);
-    if (t > (int64_t)0x1fffffff) return hipErrorInvalidValue;
     if (edge == 256) slots = 5;
-    else if (slots == 0) slots = (edge == 128) ? (t <= cus ? 10 : 5) : (t <= cus ? 20 : (t <= 2 * (int64_t)cus ? 10 : 5));
-    const dim3 grid((unsigned)(a.tiles_per_xcd * 8)), block(momk::k4Threads);
-#define MOM_LAUNCH4(E, S) hipLaunchKernelGGL((momk::gemm4_kernel<EPI, E, S>), grid, block, 0, st, a)
-    if (edge == 256 && slots == 5) {
-        if constexpr (EPI == momk::EPI_DOWN) {
-            if (width == 224) hipLaunchKernelGGL((momk::gemm4_kernel<EPI, 256, 5, 224>), grid, block, 0, st, a);
-            else if (width == 192) hipLaunchKernelGGL((momk::gemm4_kernel<EPI, 256, 5, 192>), grid, block, 0, st, a);
-            else if (width == 160) hipLaunchKernelGGL((momk::gemm4_kernel<EPI, 256, 5, 160>), grid, block, 0, st, a);
-            else if (width == 128) hipLaunchKernelGGL((momk::gemm4_kernel<EPI, 256, 5, 128>), grid, block, 0, st, a);
-            else MOM_LAUNCH4(256, 5);
-        } else {
-            MOM_LAUNCH4(256, 5);
+    else if (slots == 0) {
+        const int64_t t = tiles_of(edge, edge / gu);
+        slots = (edge == 128) ? (t <= cus ? 10 : 5) : (t <= cus ? 20 : (t <= 2 * (int64_t)cus ? 10 : 5));
+    }
+    if constexpr (EPI == momk::EPI_GATEUP) {
+        if (narrow_tiles_n > 0) {
+            const int64_t rest = (int64_t)N - 96 * narrow_tiles_n;
+            const int wide_cols = rest > 0 ? (int)((rest + 127) / 128) * 128 : 0;     // columns [0, wide_cols) in wide tiles
+            if (wide_cols >= N) return launch_gemm_form<EPI>(a, 256, 5, 256, st);
+            momk::GemmArgs2 p;
+            p.narrow = a;
+            p.narrow.W0 = W0 + (size_t)wide_cols * K;
+            p.narrow.W1 = W1 + (size_t)wide_cols * K;
+            p.narrow.O = O + wide_cols;
+            p.narrow.N = N - wide_cols;
+            if (wide_cols == 0) return launch_gemm_form<EPI>(p.narrow, 256, 5, 192, st);
+            p.wide = a;
+            p.wide.N = wide_cols;
+            if (!set_tile_grid<EPI>(p.wide, 256, 256) || !set_tile_grid<EPI>(p.narrow, 256, 192)) return hipErrorInvalidValue;
+            const int64_t wgs = 8 * ((int64_t)p.wide.tiles_per_xcd + p.narrow.tiles_per_xcd);
+            if (wgs > (int64_t)0x7fffffff) return hipErrorInvalidValue;
+            hipLaunchKernelGGL((momk::gemm4_two_width_kernel<EPI, 192>), dim3((unsigned)wgs), dim3(momk::k4Threads), 0, st, p);
+            return hipGetLastError();
         }
     }
-    else if (edge == 128 && slots == 5) MOM_LAUNCH4(128, 5);
-    else if (edge == 128 && slots == 10) MOM_LAUNCH4(128, 10);
-    else if (edge == 64 && slots == 5) MOM_LAUNCH4(64, 5);
-    else if (edge == 64 && slots == 10) MOM_LAUNCH4(64, 10);
-    else if (edge == 64 && slots == 20) MOM_LAUNCH4(64, 20);
-    else return hipErrorInvalidValue;
-#undef MOM_LAUNCH4
-    return hipGetLastError();
+    return launch_gemm_form<EPI>(a, edge, slots, width, st);
 }
 
 template <int MODE>
@@ -322,15 +386,15 @@ int mom_init(void) {
     return MOM_OK;
 }
 
-int mom_debug_force_gemm_form(int tile_edge, int ring_slots, int down_width) {
-    const bool wok = down_width == 0 || (tile_edge == 256 && (down_width == 256 || down_width == 224 || down_width == 192 ||
-                                                              down_width == 160 || down_width == 128));
+int mom_debug_force_gemm_form(int tile_edge, int ring_slots, int tile_width) {
+    const bool wok = tile_width == 0 || (tile_edge == 256 && (tile_width == 256 || tile_width == 224 || tile_width == 192 ||
+                                                              tile_width == 160 || tile_width == 128));
     const bool ok = wok && ((tile_edge == 0 && ring_slots == 0) ||
                     (tile_edge == 256 && (ring_slots == 0 || ring_slots == 5)) ||
                     (tile_edge == 128 && (ring_slots == 0 || ring_slots == 5 || ring_slots == 10)) ||
                     (tile_edge == 64 && (ring_slots == 0 || ring_slots == 5 || ring_slots == 10 || ring_slots == 20)));
     if (!ok) return MOM_ERR_SHAPE;
-    g_force_width.store(down_width, std::memory_order_relaxed);
+    g_force_width.store(tile_width, std::memory_order_relaxed);
     g_force_slots.store(ring_slots, std::memory_order_relaxed);
     g_force_edge.store(tile_edge, std::memory_order_relaxed);
     return MOM_OK;

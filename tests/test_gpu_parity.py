@@ -89,7 +89,7 @@ def gemm_form():
 
 
 FORMS = ((256, 5), (128, 5), (128, 10), (64, 5), (64, 10), (64, 20),
-         # 256-row tiles with 224 ... 128 weight rows for the down projection
+         # 256-row tiles with 224 ... 128 weight rows for the down projection (192: also 96-column gate/up tiles)
          (256, 5, 224), (256, 5, 192), (256, 5, 160), (256, 5, 128))
 
 
@@ -670,6 +670,30 @@ def test_gemm_tile_forms_give_identical_bits(S, H, I, gemm_form):
     for i, o in enumerate(outs[1:]):
         assert bits_equal(outs[0], o), f"form {i + 1}"
     assert_close_to_oracle(_f32(outs[0]), ref, f"tile forms S={S} H={H} I={I}")
+
+
+@pytest.mark.parametrize("S,H,I", [(1024, 128, 14336), (1000, 96, 14304), (2048, 64, 14336), (1024, 128, 9472)])
+def test_gate_up_column_split_gives_identical_bits(S, H, I, gemm_form):
+    """Where the 256 x 128 gate/up tiles of a launch fill the CUs in a fraction of a round more than whole
+    rounds, the library runs the first columns in tiles of 128 columns and the rest in tiles of 96, as two
+    launches (4 token tiles x 14336 columns: 448 tiles = 1.75 rounds become one round of each width).
+    Same bits as one width throughout, wide or narrow, and the oracle's values on sampled rows."""
+    dev = _dev()
+    wl = synth.Workload("split", S=S, H=H, I=I, mini_seq=0, seed=S + I, w_std=0.05)
+    x, wg, wu, wd = synth.mlp_inputs(wl, device=dev)
+    gemm_form(0, 0)
+    auto, _ = run_mlp(x, wg, wu, wd, 0)
+    for form in ((256, 5, 256), (256, 5, 192), (128, 5)):
+        gemm_form(*form)
+        o, _ = run_mlp(x, wg, wu, wd, 0)
+        assert bits_equal(o, auto), f"form {form}"
+    gemm_form(0, 0)
+    o, _ = run_mlp(x, wg, wu, wd, 300)
+    assert bits_equal(o, auto), "mini_seq 300"
+    rows = synth.parity_rows(S, 0, n_random=16, seed=5, residues=256)
+    rows_t = torch.from_numpy(rows).to(dev)
+    ref = oracle.mlp_rows(synth.bits(x[rows_t]), synth.bits(wg), synth.bits(wu), synth.bits(wd))
+    assert_close_to_oracle(_f32(auto[rows_t]), ref, f"gate/up column split S={S} H={H} I={I}")
 
 
 def test_forced_form_validation(gemm_form):
