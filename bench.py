@@ -116,7 +116,7 @@ def mfma_probe(binding, torch, tensors, dev):
     ones = torch.ones(4096, dtype=torch.bfloat16, device=dev)
     res = {}
     for name, a, b in (("workload_operands", wg, x), ("constant_operands", ones, ones)):
-        iters = 60000                                      # ~35 ms per launch at 1.9 GHz
+        iters = 30000                                      # ~35 ms per launch at 1.9 GHz
         flop = None
 
         def launch():

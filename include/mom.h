@@ -233,11 +233,12 @@ int mom_debug_force_pipeline(int on);
 
 /*
  * Measurement aid: the rate the matrix cores of this machine sustain on given operand values.
- * Launches `workgroups` workgroups of 4 wavefronts (one per SIMD); every wavefront fills 8 + 8
+ * Launches `workgroups` workgroups of 4 wavefronts (one per SIMD); every wavefront fills 16 + 16
  * operand fragments once from a_bf16 / b_bf16 (device, bf16, a_bytes / b_bytes >= 16 and
- * multiples of 16 are used; indices wrap) and then runs `iters` times 64
- * v_mfma_f32_16x16x32_bf16 on 64 accumulator blocks in registers - no LDS, no memory traffic.
- *   flop of a launch = workgroups * 4 * iters * 64 * 16384
+ * multiples of 16 are used; indices wrap) and then runs `iters` times 128
+ * v_mfma_f32_16x16x32_bf16 - two in a row on each of 64 accumulator blocks in registers, the
+ * order of the matrix-core kernels - with no LDS and no memory traffic.
+ *   flop of a launch = workgroups * 4 * iters * 128 * 16384
  *   sink   device, at least workgroups * 256 floats; receives one checksum per lane
  * Timed by the caller with events on `stream`.  The power an MFMA draws depends on the values
  * it multiplies, and the chip sets its clock by its power limit, so the rate measured here on a

@@ -194,7 +194,7 @@ def mom_debug_mfma_probe(a, b, iters, workgroups, sink, stream=None):
                                     _ptr(sink), _stream(stream))
     if rc != MOM_OK:
         raise MomError(rc, "mom_debug_mfma_probe")
-    return float(workgroups) * 4 * int(iters) * 64 * 16384
+    return float(workgroups) * 4 * int(iters) * 128 * 16384
 
 
 def mom_kv_offload(k, v, pinned_host, stream, producer_stream=None, order_event=None, done_event=None,
