@@ -64,10 +64,9 @@ struct DeviceInfo {
 };
 DeviceInfo g_dev[kMaxDevices];
 
-// Gate/up tiles of 96 columns beside those of 128: a column costs the same in either (measured: a round of
-// 256 x 96 tiles takes 0.747 of the time of a round of 256 x 128 tiles), but a last round that fills
-// only part of the CUs is not as dear as a whole one either - the chip is power-limited and clocks the
-// busy CUs higher - so the mix has to save this much of the time in whole rounds before it is used.
+// Gate/up tiles of 96 columns beside those of 128: a column of the narrow tile costs 7 % more (measured over
+// whole rounds), and the mix has to save this much of the modelled time before it is used.
+constexpr int kGateUpNarrowPerMille = 1070;
 constexpr int kGateUpMixMinGainPerMille = 15;
 
 // Testing overrides (mom_debug_force_gemm_form / mom_debug_force_pipeline); 0 = the library chooses.
@@ -182,14 +181,14 @@ hipError_t launch_gemm(const unsigned short* X, const unsigned short* W0, const 
     // the CUs without work; then 128-tiles, or 64-tiles when even those fill less than half of the CUs;
     // the small tiles get a deeper ring the fewer workgroups a CU has to hide latency with.
     // Down projection with 256-row tiles: 256, 224, 192, 160 or 128 weight rows per tile, whichever needs
-    // the least time in whole rounds of the CUs (rounds x width, a narrower tile charged a little more per
-    // column for the token fragments it shares among fewer MFMAs): 3584 output columns with 32 token tiles
-    // are 1.75 rounds of 256-wide tiles on 256 CUs but exactly 2 rounds of 224-wide ones, and the 128
-    // full-size tiles of a 2048-row mini-sequence at 4096 columns are one round of 256 tiles 128 wide.
+    // the least time in rounds of the CUs (rounds x width, a narrower tile charged more per column for the
+    // token fragments it shares among fewer MFMAs, a partly filled last round less than a whole one): 3584
+    // output columns with 32 token tiles are 1.75 rounds of 256-wide tiles on 256 CUs but exactly 2 rounds
+    // of 224-wide ones, and the 128 full-size tiles of a 2048-row mini-sequence at 4096 columns are one
+    // round of 256 tiles 128 wide.
     // Gate/up with 256-row tiles: the first columns in tiles of 128 columns, the rest in tiles of 96, in one
-    // launch of the two-width kernel, where that saves time in whole rounds: 14336 columns with 4 token
-    // tiles are 448 tiles = 1.75 rounds -> 2, but 64 x 128 + 64 x 96 columns are one round of each width
-    // = 1.75 rounds' time.
+    // launch of the two-width kernel, where the same model says that saves time: 14336 columns with 12 token
+    // tiles are 1344 tiles = 5.25 rounds, but 64 x 128 + 64 x 96 columns are three rounds of each width.
     // mom_debug_force_gemm_form overrides the choice (for tests, which need every form on shapes of
     // every size).
     const int cus = compute_units();
@@ -204,10 +203,17 @@ hipError_t launch_gemm(const unsigned short* X, const unsigned short* W0, const 
         if (edge == 256 && fw && (EPI == momk::EPI_DOWN || fw == 192)) width = fw;
         slots = g_force_slots.load(std::memory_order_relaxed);
     } else {
-        // time in units of 1/1000 of a 256 x 256 tile: rounds x width x (1 + what the narrower tile costs per column)
+        // Rounds of the CUs a launch of `tiles` tiles takes, in 1/1000.  A last round that fills only part of the
+        // CUs is not as dear as a whole one: the chip is power-limited and clocks the busy CUs higher (measured:
+        // a round on a quarter / half / three quarters of the CUs takes about 0.55 / 0.8 / 0.8-0.9 of a full one).
+        auto rounds_pm = [&](int64_t tiles) {
+            const int64_t full = tiles / cus, rem = tiles % cus;
+            return full * 1000 + (rem ? 500 + 500 * rem / cus : 0);
+        };
+        // time in units of 1e-6 of a 256 x 256 tile per column: rounds x width x (1 + what the narrower tile costs per column)
         auto down_cost = [&](int w) {
-            static const int per_mille[5] = {1000, 1030, 1030, 1050, 1240};     // 256, 224, 192, 160, 128 (measured)
-            return ((tiles_of(256, w) + cus - 1) / cus) * w * per_mille[(256 - w) / 32];
+            static const int per_mille[5] = {1000, 1020, 1070, 1170, 1310};     // 256, 224, 192, 160, 128 (measured)
+            return rounds_pm(tiles_of(256, w)) * w * per_mille[(256 - w) / 32];
         };
         int64_t best = 0;
         if (EPI == momk::EPI_DOWN && !never_small)       // (beside a chip-filling gate/up kernel: full-size tiles, however few)
@@ -225,7 +231,7 @@ hipError_t launch_gemm(const unsigned short* X, const unsigned short* W0, const 
             auto cost = [&](int64_t b) {
                 const int64_t rest = (int64_t)N - 96 * b;
                 const int64_t wide = rest > 0 ? (rest + 127) / 128 : 0;
-                return ((tm * wide + cus - 1) / cus) * 128 + ((tm * b + cus - 1) / cus) * 96;
+                return rounds_pm(tm * wide) * 128 * 1000 + rounds_pm(tm * b) * 96 * kGateUpNarrowPerMille;
             };
             const int64_t plain = cost(0);
             int64_t best_cost = plain;
