@@ -7,7 +7,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmom.so")
 SOURCES = [os.path.join(CSRC, "mom.hip")]
-DEPS = SOURCES + [os.path.join(CSRC, "mom_gemm.hip.inc"),
+DEPS = SOURCES + [os.path.join(CSRC, "mom_gemm.hip.inc"), os.path.join(CSRC, "mom_gemm_schedule.h"),
                   os.path.join(CSRC, "mom_gemv.hip.inc"), os.path.join(CSRC, "mom_probe.hip.inc"),
                   os.path.join(ROOT, "include", "mom.h")]
 

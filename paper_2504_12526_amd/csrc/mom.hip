@@ -11,6 +11,7 @@
 #include <type_traits>
 
 #include "mom.h"
+#include "mom_gemm_schedule.h"
 #include "mom_gemm.hip.inc"
 #include "mom_gemv.hip.inc"
 #include "mom_probe.hip.inc"
