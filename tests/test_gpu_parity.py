@@ -157,6 +157,31 @@ def test_ragged_shapes_match_oracle(S, H, I):
         assert bits_equal(out, full), f"C={C}"
 
 
+def test_seeded_random_shapes_on_the_256_row_tiles(gemm_form):
+    """Twenty seeded random shapes (rows, H and I any multiple of 32 - so contraction lengths with and without a
+    final half stage, ragged row and column tiles, one to a dozen stages) through the 256-row tile forms of every
+    width, which is where the hand-laid stage schedule lives: full tensor against the oracle, every width and a
+    random mini-sequence length against each other bit for bit."""
+    dev = _dev()
+    rng = np.random.default_rng(20250412)
+    for case in range(20):
+        S = int(rng.integers(1, 900))
+        H = 32 * int(rng.integers(1, 25))
+        I = 32 * int(rng.integers(1, 25))
+        C = int(rng.integers(1, S + 1))
+        wl = synth.Workload("rnd", S=S, H=H, I=I, mini_seq=0, seed=1000 + case, w_std=0.05)
+        x, wg, wu, wd = synth.mlp_inputs(wl)
+        ref = oracle.mlp_rows(*(synth.bits(t) for t in (x, wg, wu, wd)))
+        xd, wgd, wud, wdd = (t.to(dev) for t in (x, wg, wu, wd))
+        gemm_form(256, 5, 256)
+        base, _ = run_mlp(xd, wgd, wud, wdd, 0)
+        assert_close_to_oracle(_f32(base), ref, f"case {case}: S={S} H={H} I={I}")
+        for w in (224, 192, 160, 128):
+            gemm_form(256, 5, w)
+            o, _ = run_mlp(xd, wgd, wud, wdd, C if w in (192, 128) else 0)
+            assert bits_equal(o, base), f"case {case}: S={S} H={H} I={I} width {w}"
+
+
 @pytest.mark.parametrize("S,H,I", [(300, 96, 160), (257, 64, 64), (700, 384, 640), (1100, 256, 1024), (2500, 512, 512)])
 def test_pipelined_schedule_gives_the_same_bits(S, H, I, forced_pipeline):
     """Two streams and a double-buffered workspace change the schedule, not one bit of the result.
