@@ -115,13 +115,14 @@ def mfma_probe(binding, torch, tensors, dev):
     sink = torch.empty(cus * 256, dtype=torch.float32, device=dev)
     ones = torch.ones(4096, dtype=torch.bfloat16, device=dev)
     res = {}
-    for name, a, b in (("workload_operands", wg, x), ("constant_operands", ones, ones)):
+    for name, a, b, order in (("workload_operands", wg, x, 0), ("workload_operands_k_half_by_k_half", wg, x, 1),
+                              ("constant_operands", ones, ones, 0)):
         iters = 30000                                      # ~35 ms per launch at 1.9 GHz
         flop = None
 
         def launch():
             nonlocal flop
-            flop = binding.mom_debug_mfma_probe(a, b, iters, cus, sink)
+            flop = binding.mom_debug_mfma_probe(a, b, iters, cus, sink, order=order)
         t = event_time(torch, launch, reps=8, warmup=3)    # ~0.1 s of warm-up: the clock has settled
         res[name] = round(flop / t / 1e12, 1)
     return res
@@ -459,10 +460,12 @@ def main():
         rf = result["roofline"]
         rf["sustained_peak"] = probe["workload_operands"]
         rf["sustained_peak_constant_operands"] = probe["constant_operands"]
+        rf["sustained_peak_k_half_by_k_half"] = probe["workload_operands_k_half_by_k_half"]
         rf["frac_sustained"] = round(gu_tflops / probe["workload_operands"], 4)
         rf["sustained_peak_note"] = ("register-only v_mfma_f32_16x16x32_bf16 loop on all CUs (mom_debug_mfma_probe), operand "
-                                     "fragments from this workload's W_gate and x; with constant operands the same loop is not "
-                                     "power-limited")
+                                     "fragments from this workload's W_gate and x, MFMAs in the kernels' order (both K-halves of a "
+                                     "stage into an accumulator block back to back); k_half_by_k_half: the same MFMAs in the order "
+                                     "the kernels used before; with constant operands the loop is not power-limited")
         result["whole_step_frac_sustained"] = round(tflops / probe["workload_operands"], 4)
         result["power"] = power_under_load(binding, torch, tensors, C, out, ws, S, H, I)
         side = {}

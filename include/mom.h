@@ -236,8 +236,11 @@ int mom_debug_force_pipeline(int on);
  * Launches `workgroups` workgroups of 4 wavefronts (one per SIMD); every wavefront fills 16 + 16
  * operand fragments once from a_bf16 / b_bf16 (device, bf16, a_bytes / b_bytes >= 16 and
  * multiples of 16 are used; indices wrap) and then runs `iters` times 128
- * v_mfma_f32_16x16x32_bf16 - two in a row on each of 64 accumulator blocks in registers, the
- * order of the matrix-core kernels - with no LDS and no memory traffic.
+ * v_mfma_f32_16x16x32_bf16 on 64 accumulator blocks in registers, with no LDS and no memory
+ * traffic.  order 0: two in a row on each block (the two K-halves of a stage), the order of the
+ * matrix-core kernels; order 1: the first of each pair on all 64 blocks, then the second (what the
+ * kernels did before: the difference is what accumulating back to back saves).  Other values:
+ * MOM_ERR_SHAPE.
  *   flop of a launch = workgroups * 4 * iters * 128 * 16384
  *   sink   device, at least workgroups * 256 floats; receives one checksum per lane
  * Timed by the caller with events on `stream`.  The power an MFMA draws depends on the values
@@ -246,7 +249,7 @@ int mom_debug_force_pipeline(int on);
  * as opposed to the datasheet peak at the maximum clock.
  */
 int mom_debug_mfma_probe(const void *a_bf16, size_t a_bytes, const void *b_bf16, size_t b_bytes,
-                         int64_t iters, int workgroups, float *sink, void *stream);
+                         int64_t iters, int workgroups, int order, float *sink, void *stream);
 
 #ifdef __cplusplus
 }

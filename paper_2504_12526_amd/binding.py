@@ -71,7 +71,7 @@ def lib():
         L.mom_debug_force_gemm_form.restype = ctypes.c_int
         L.mom_debug_force_gemm_form.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int]
         L.mom_debug_mfma_probe.restype = ctypes.c_int
-        L.mom_debug_mfma_probe.argtypes = [vp, sz, vp, sz, i64, ctypes.c_int, vp, vp]
+        L.mom_debug_mfma_probe.argtypes = [vp, sz, vp, sz, i64, ctypes.c_int, ctypes.c_int, vp, vp]
         L.mom_debug_force_pipeline.restype = ctypes.c_int
         L.mom_debug_force_pipeline.argtypes = [ctypes.c_int]
         _lib = L
@@ -185,13 +185,14 @@ def mom_debug_force_pipeline(on):
     return lib().mom_debug_force_pipeline(1 if on else 0)
 
 
-def mom_debug_mfma_probe(a, b, iters, workgroups, sink, stream=None):
-    """Measurement aid: register-only MFMA loop on operand fragments taken from bf16 tensors a and b;
-    returns the flop of the launch (time it with events on the stream)."""
+def mom_debug_mfma_probe(a, b, iters, workgroups, sink, stream=None, order=0):
+    """Measurement aid: register-only MFMA loop on operand fragments taken from bf16 tensors a and b
+    (order 0: the kernels' back-to-back pairs, 1: K-half by K-half); returns the flop of the launch
+    (time it with events on the stream)."""
     if sink.numel() < workgroups * 256 or sink.dtype != torch.float32:
         raise ValueError("sink must hold workgroups*256 float32")
     rc = lib().mom_debug_mfma_probe(_ptr(a), _nbytes(a), _ptr(b), _nbytes(b), int(iters), int(workgroups),
-                                    _ptr(sink), _stream(stream))
+                                    int(order), _ptr(sink), _stream(stream))
     if rc != MOM_OK:
         raise MomError(rc, "mom_debug_mfma_probe")
     return float(workgroups) * 4 * int(iters) * 128 * 16384

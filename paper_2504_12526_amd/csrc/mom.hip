@@ -408,16 +408,22 @@ int mom_debug_force_gemm_form(int tile_edge, int ring_slots, int tile_width) {
 }
 
 int mom_debug_mfma_probe(const void* a_bf16, size_t a_bytes, const void* b_bf16, size_t b_bytes, int64_t iters,
-                         int workgroups, float* sink, void* stream) {
+                         int workgroups, int order, float* sink, void* stream) {
     if (!a_bf16 || !b_bf16 || !sink) return MOM_ERR_NULL;
     if (!aligned16(a_bf16) || !aligned16(b_bf16) || !aligned16(sink)) return MOM_ERR_ALIGN;
     if (a_bytes < 16 || b_bytes < 16 || a_bytes / 16 > 0x7fffffffu || b_bytes / 16 > 0x7fffffffu || iters < 0 ||
-        workgroups <= 0 || workgroups > (1 << 20))
+        workgroups <= 0 || workgroups > (1 << 20) || (order != 0 && order != 1))
         return MOM_ERR_SHAPE;
-    hipLaunchKernelGGL(momk::mfma_probe_kernel, dim3((unsigned)workgroups), dim3(momk::kProbeThreads), 0,
-                       static_cast<hipStream_t>(stream), static_cast<const momk::u32x4*>(a_bf16),
-                       (unsigned)(a_bytes / 16), static_cast<const momk::u32x4*>(b_bf16), (unsigned)(b_bytes / 16),
-                       (long long)iters, sink);
+    const dim3 grid((unsigned)workgroups), block(momk::kProbeThreads);
+    const momk::u32x4* a = static_cast<const momk::u32x4*>(a_bf16);
+    const momk::u32x4* b = static_cast<const momk::u32x4*>(b_bf16);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (order == 0)
+        hipLaunchKernelGGL(momk::mfma_probe_kernel<0>, grid, block, 0, st, a, (unsigned)(a_bytes / 16), b,
+                           (unsigned)(b_bytes / 16), (long long)iters, sink);
+    else
+        hipLaunchKernelGGL(momk::mfma_probe_kernel<1>, grid, block, 0, st, a, (unsigned)(a_bytes / 16), b,
+                           (unsigned)(b_bytes / 16), (long long)iters, sink);
     return hipGetLastError() == hipSuccess ? MOM_OK : MOM_ERR_HIP;
 }
 

@@ -842,6 +842,7 @@ def test_bench_prints_the_contract_json_line():
     assert d["cpu_baseline"]["parity_in_bench"]["ok"] is True
     # side measurements (outside the timed region) travel in the same line
     assert d["roofline"]["sustained_peak"] > 0 and d["roofline"]["sustained_peak_constant_operands"] > 0
+    assert d["roofline"]["sustained_peak_k_half_by_k_half"] > 0
     assert abs(d["roofline"]["frac_sustained"] - d["roofline"]["achieved"] / d["roofline"]["sustained_peak"]) < 1e-3
     for k in ("mini_seq_sweep", "peak_memory", "lmhead", "last_token_mlp", "last_token_branch", "kv_offload"):
         assert k in d["side"], k
